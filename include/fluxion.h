@@ -1,0 +1,137 @@
+/* fluxion.h -- C ABI of the MI355X block-sparse decode-attention library (libfluxion.so).
+ *
+ * The library implements, as HIP kernels for gfx950, the per-step hot path of block-sparse attention
+ * over a long KV cache as the paper states it (Sec. 2.1): the cache of every KV head is cut into
+ * logical blocks, each block is represented by the per-channel minimum and maximum of its keys, a
+ * decode query is compared with that metadata to rank the blocks, the top-k blocks are chosen, and
+ * attention runs over the tokens of the chosen blocks only.  The first tokens (sink) and the most
+ * recent tokens (local window) are always attended to, and their contribution is fused with that of
+ * the chosen blocks (Sec. 2.2, Sec. 3.2, Sec. 4 step 4).  Under GQA all query heads of a group share
+ * the block size of their KV head while every query head has its own budget (Sec. 5.3).
+ *
+ * Conventions
+ *   - Plain C types only.  bf16 tensors are passed as `const void*` / `void*` to 2-byte elements;
+ *     `stream` is a hipStream_t passed as `void*` (NULL = the default stream).
+ *   - Unless a parameter says HOST, every pointer is a DEVICE pointer owned by the caller.  The
+ *     library allocates nothing, frees nothing and never synchronises: every call only enqueues
+ *     kernels on `stream` and returns.  Buffers must stay valid until that work has finished.
+ *   - All arguments that can be checked without touching the device are checked before the first HIP
+ *     call; a failed check returns an error code and enqueues nothing.  No call aborts or throws.
+ *   - Inputs are assumed finite.
+ *
+ * Geometry of one (sequence b, KV head j) with N = seq_len[b] tokens and block size g = gran[j]:
+ *   blocks            i = 0 .. ceil(N / g) - 1, block i holds tokens [i*g, min((i+1)*g, N))
+ *   sink blocks       i <  n_sink = ceil(sink_tokens / g)
+ *   window blocks     i >= w0     = floor(max(N - window_tokens, 0) / g)
+ *   candidate blocks  n_sink <= i < w0   (n_cand = max(w0 - n_sink, 0)); only these are ranked.
+ */
+#ifndef FLUXION_H
+#define FLUXION_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum fx_status {
+  FX_OK = 0,
+  FX_ERR_INVALID_ARG = 1,         /* null pointer, inconsistent sizes, misaligned pointer or stride      */
+  FX_ERR_UNSUPPORTED = 2,         /* head_dim, group size, block size or context outside the built range */
+  FX_ERR_WORKSPACE_TOO_SMALL = 3, /* workspace_bytes below what fx_*_workspace_bytes reports              */
+  FX_ERR_HIP = 4                  /* a HIP launch failed; hipGetLastError() has the cause                 */
+} fx_status;
+
+/* Static, never-NULL description of a status code. */
+const char* fx_status_string(fx_status status);
+
+/* Placement of one layer's KV cache.  Element (b, j, t, c) of K (and of V) is at
+ *     K[seq_base[b] + j * kv_head_stride + t * token_stride + c],   0 <= c < head_dim,
+ * so head-major, token-major and ragged (unpadded) batches are all expressible.  The summary of block
+ * i of (b, j) is the pair of rows
+ *     S[((sum_base[b * n_kv_heads + j] + i) * 2 + 0) * head_dim + c]   (minimum)
+ *     S[((sum_base[b * n_kv_heads + j] + i) * 2 + 1) * head_dim + c]   (maximum).
+ * Supported: head_dim 64 or 128; n_q_heads a multiple of n_kv_heads with group size <= 8;
+ * n_kv_heads <= 64; gran[j] a multiple of 16 in [16, 128]; max_seq_len <= 2^20.
+ * Alignment: K, V, S and q 16-byte aligned; token_stride, kv_head_stride and every seq_base[b]
+ * multiples of 8 elements; token_stride >= head_dim.
+ */
+typedef struct fx_layout {
+  int32_t batch;
+  int32_t n_q_heads;
+  int32_t n_kv_heads;
+  int32_t head_dim;
+  int32_t max_seq_len;     /* HOST bound: seq_len[b] <= max_seq_len.  Longer entries are clamped to it.   */
+  const int32_t* seq_len;  /* DEVICE [batch]              valid tokens per sequence                        */
+  const int64_t* seq_base; /* DEVICE [batch]              element offset of sequence b in K and in V       */
+  int64_t kv_head_stride;  /* elements                                                                     */
+  int64_t token_stride;    /* elements                                                                     */
+  const int64_t* sum_base; /* DEVICE [batch * n_kv_heads] block offset of (b, j) in the summaries          */
+  const int32_t* gran;     /* HOST   [n_kv_heads]         logical block size g_j                           */
+} fx_layout;
+
+/* Block key summaries (Sec. 2.1: per block, the dimension-wise maxima and minima of its token keys).
+ * Reads every valid key once and writes, for every block of every (b, j), the minimum row and the
+ * maximum row over the block's valid tokens (a partial last block covers its valid tokens only).
+ * The values written are elements of K, bit for bit (for +-0 either sign may be kept).
+ *   K          bf16, placed as fx_layout says
+ *   summaries  bf16, written; must hold max over (b, j) of sum_base + ceil(seq_len/g) blocks
+ * Errors: INVALID_ARG (null/misaligned), UNSUPPORTED (layout outside the supported range), HIP. */
+fx_status fx_summarize(const fx_layout* layout, const void* K, void* summaries, void* stream);
+
+/* Bytes of scratch fx_select needs for this layout (HOST computation, depends on batch, n_q_heads,
+ * max_seq_len and gran only).  Returns 0 if the layout is invalid. */
+size_t fx_select_workspace_bytes(const fx_layout* layout);
+
+/* Block scoring and per-head top-k (Sec. 2.1: compare the query with the metadata of all key blocks,
+ * then select the top-k blocks; Sec. 5.3: one block size per group, one budget per head).
+ * For query head h of sequence b (KV head j = h / group) and every candidate block i
+ *     score(i) = sum_c max(q[c] * min_i[c], q[c] * max_i[c])          (accumulated in fp64)
+ * and the k_h candidates that come first in the order (score descending, index ascending) are kept,
+ * with k_h = budget_blocks[b][h] if given, else ceil(budget_frac[b][h] * n_cand) evaluated in double,
+ * clamped to [0, min(n_cand, k_max)].
+ *   q              bf16 [batch][n_q_heads][head_dim]
+ *   summaries      bf16, as written by fx_summarize for the same layout
+ *   budget_frac    float [batch][n_q_heads], or NULL   } exactly one of the two
+ *   budget_blocks  int32 [batch][n_q_heads], or NULL   } is non-NULL
+ *   idx            int32 [batch][n_q_heads][k_max], written: the kept block indices in ascending
+ *                  order, then -1 up to k_max
+ *   cnt            int32 [batch][n_q_heads], written: k_h
+ *   workspace      >= fx_select_workspace_bytes(layout) bytes, 16-byte aligned; contents undefined after
+ * A budget of 0 keeps nothing (streaming head: only sink and window are attended, Sec. 3.2); a budget
+ * of 1.0 keeps every candidate, which makes the later attention dense.
+ * Errors: INVALID_ARG (null/misaligned, both or neither budget, k_max < 1, negative sink/window),
+ * UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP. */
+fx_status fx_select(const fx_layout* layout, const void* q, const void* summaries, const float* budget_frac,
+                    const int32_t* budget_blocks, int32_t sink_tokens, int32_t window_tokens, int32_t k_max,
+                    int32_t* idx, int32_t* cnt, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of scratch fx_sparse_decode needs (HOST computation; depends on the layout's host fields,
+ * k_max, sink_tokens and window_tokens).  Returns 0 if the arguments are invalid. */
+size_t fx_decode_workspace_bytes(const fx_layout* layout, int32_t k_max, int32_t sink_tokens, int32_t window_tokens);
+
+/* Split-K sparse decode attention with online-softmax merge (App. A.1: s = q K^T / sqrt(D),
+ * O = softmax(s) V, restricted to the kept tokens; Sec. 2.2 / Sec. 4 step 4: the partial results
+ * over the chosen blocks and over the retained sink and window tokens are fused into one output).
+ * Query head h of sequence b attends to the valid tokens of: its own chosen blocks
+ * idx[b][h][0 .. cnt[b][h]), every sink block and every window block.  The blocks the heads of one
+ * group need are read from HBM once per group; partial (max, sum, accumulator) triples of the splits
+ * are merged in a fixed order, so results are reproducible run to run.
+ *   q          bf16 [batch][n_q_heads][head_dim]
+ *   K, V       bf16, placed as fx_layout says
+ *   idx, cnt   as produced by fx_select, or any list of block indices; entries outside
+ *              [0, n_blocks) are ignored, duplicates and entries inside sink/window are harmless,
+ *              cnt is clamped to [0, k_max]
+ *   out        float [batch][n_q_heads][head_dim], written (zeros for a sequence of length 0)
+ *   workspace  >= fx_decode_workspace_bytes(...) bytes, 16-byte aligned; contents undefined after
+ * Arithmetic: bf16 inputs, fp32 products, sums, exponentials and accumulators.
+ * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP. */
+fx_status fx_sparse_decode(const fx_layout* layout, const void* q, const void* K, const void* V, const int32_t* idx,
+                           const int32_t* cnt, int32_t k_max, int32_t sink_tokens, int32_t window_tokens, float* out,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLUXION_H */

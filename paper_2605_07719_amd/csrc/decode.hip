@@ -1,0 +1,353 @@
+// Split-K sparse decode attention with an online-softmax merge (App. A.1 of the paper:
+// s = q K^T / sqrt(D), O = softmax(s) V over the kept tokens; Sec. 2.2 and Sec. 4 step 4: the result
+// over the chosen blocks is fused with the result over the retained sink and window tokens; Sec. 5.3
+// and Sec. 6.2: the unit of work is one GQA group of one sequence).
+//
+// Three kernels on one stream:
+//   plan_kernel    per (sequence, KV head): OR the chosen-block lists of the group's heads into a
+//                  per-block head mask, add the sink and window blocks for every head, and compact
+//                  the non-empty blocks into an ascending "union list" of (block, head mask) entries.
+//                  A block that several heads of the group want is then read from HBM once.
+//   attend_kernel  persistent workgroups walk work items; an item is a chunk of one group's union
+//                  list.  Each wave takes 16-token slices of the chunk: coalesced 16-byte-per-lane
+//                  loads of K and V rows, fp32 dot products reduced inside the 8/16 lanes that share
+//                  a token, running (max, sum, accumulator) per head in registers.  Per item one
+//                  partial triple per head is written.  The chunk length adapts to the total amount
+//                  of selected work so that small steps still spread over the whole chip.
+//   merge_kernel   per (sequence, query head): fuse the partial triples of the group's items in
+//                  item order (fixed order => reproducible results).
+// Logits are kept in the log2 domain (q is pre-multiplied by log2(e)/sqrt(D)) so the exponentials
+// are single v_exp_f32 instructions.
+#include "fx_device.hpp"
+#include "fx_kernels.hpp"
+
+namespace fx {
+
+__global__ __launch_bounds__(256) void plan_kernel(Params P, const int32_t* __restrict__ idx,
+                                                   const int32_t* __restrict__ cnt, uint32_t* __restrict__ uni,
+                                                   int32_t* __restrict__ ucount, int union_cap) {
+  extern __shared__ uint32_t mask_words[];  // one byte of head mask per block, 4 blocks per word
+  __shared__ int scratch[4];
+  const int b = blockIdx.y, j = blockIdx.x, tid = threadIdx.x;
+  const int grp = b * P.n_kv_heads + j;
+  const Geo geo = geometry(P, b, j);
+  const int n_words = (geo.n_blocks + 3) >> 2;
+  for (int w = tid; w < n_words; w += 256) mask_words[w] = 0u;
+  __syncthreads();
+  for (int r = 0; r < P.group; ++r) {
+    const int64_t slot = (int64_t)b * P.n_q_heads + j * P.group + r;
+    int c = cnt[slot];
+    c = c < 0 ? 0 : (c > P.k_max ? P.k_max : c);
+    for (int e = tid; e < c; e += 256) {
+      const int i = idx[slot * P.k_max + e];
+      if (i >= 0 && i < geo.n_blocks) atomicOr(&mask_words[i >> 2], (1u << r) << ((i & 3) * 8));
+    }
+  }
+  __syncthreads();
+  const uint32_t all = (1u << P.group) - 1u;
+  int run = 0;
+  for (int base = 0; base < geo.n_blocks; base += 256) {
+    const int i = base + tid;
+    uint32_t m = 0;
+    if (i < geo.n_blocks) {
+      m = (mask_words[i >> 2] >> ((i & 3) * 8)) & 255u;
+      if (i < geo.n_sink || i >= geo.w0) m = all;
+    }
+    int tot;
+    const int pos = run + block_excl_count(m != 0, scratch, tot);
+    if (m != 0 && pos < union_cap) uni[(int64_t)grp * union_cap + pos] = ((uint32_t)i << 8) | m;
+    run += tot;
+  }
+  if (tid == 0) ucount[grp] = run < union_cap ? run : union_cap;
+}
+
+template <int kD, int kG>
+__global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* __restrict__ q,
+                                                     const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
+                                                     const uint32_t* __restrict__ uni,
+                                                     const int32_t* __restrict__ ucount, int union_cap,
+                                                     int32_t* __restrict__ sched, float* __restrict__ acc_part,
+                                                     float* __restrict__ ml_part, int items_cap) {
+  constexpr int kLanes = kD / 8;        // lanes that share one token row
+  constexpr int kTPL = 64 / kLanes;     // token rows per wave-wide load
+  constexpr int kLoads = 16 / kTPL;     // loads per 16-token slice
+  extern __shared__ int s_prefix[];     // [n_groups + 1] exclusive prefix of items per group
+  __shared__ float s_red[4][kG][kD + 2];
+  __shared__ int s_scan[4];
+  __shared__ unsigned long long s_total;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int chunk = lane % kLanes, tslot = lane / kLanes;
+  const int n_groups = P.batch * P.n_kv_heads;
+
+  // ---- split sizing, computed identically by every workgroup -------------------------------------
+  if (tid == 0) s_total = 0ull;
+  __syncthreads();
+  {
+    unsigned long long local = 0;
+    for (int g = tid; g < n_groups; g += 256) local += (unsigned long long)ucount[g] * P.gran[g % P.n_kv_heads];
+    if (local) atomicAdd(&s_total, local);
+  }
+  __syncthreads();
+  const unsigned long long total_tokens = s_total;
+  int shift = 0;
+  while (shift < kMaxChunkShift && total_tokens > (unsigned long long)kTargetItems * (kMinChunkTokens << shift)) ++shift;
+  const int chunk_tokens = kMinChunkTokens << shift;
+  {
+    const int per = (n_groups + 255) / 256;
+    const int g_lo = min(tid * per, n_groups), g_hi = min(g_lo + per, n_groups);
+    int local = 0;
+    for (int g = g_lo; g < g_hi; ++g) {
+      const int cb = max(1, chunk_tokens / (int)P.gran[g % P.n_kv_heads]);
+      local += (ucount[g] + cb - 1) / cb;
+    }
+    const int incl = block_incl_scan(local, s_scan);
+    int run = incl - local;
+    for (int g = g_lo; g < g_hi; ++g) {
+      s_prefix[g] = run;
+      const int cb = max(1, chunk_tokens / (int)P.gran[g % P.n_kv_heads]);
+      run += (ucount[g] + cb - 1) / cb;
+    }
+    if (tid == 255) s_prefix[n_groups] = incl;  // the last thread's inclusive sum is the item total
+  }
+  __syncthreads();
+  const int n_items = min(s_prefix[n_groups], items_cap);
+  if (blockIdx.x == 0) {
+    for (int g = tid; g <= n_groups; g += 256) sched[g] = s_prefix[g];
+    if (tid == 0) sched[n_groups + 1] = chunk_tokens;
+  }
+
+  const float q_scale = 1.4426950408889634f * rsqrtf((float)kD);
+
+  for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+    // group of this item: the last g with s_prefix[g] <= item
+    int lo = 0, hi = n_groups - 1;
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (s_prefix[mid] <= item) lo = mid; else hi = mid - 1;
+    }
+    const int grp = lo, b = grp / P.n_kv_heads, j = grp % P.n_kv_heads;
+    const Geo geo = geometry(P, b, j);
+    const int cb = max(1, chunk_tokens / geo.g);
+    const int n_union = ucount[grp];
+    const int e0 = (item - s_prefix[grp]) * cb;
+    const int e1 = min(e0 + cb, n_union);
+    const int spb = geo.g >> 4;  // 16-token slices per block
+    const int n_slices = (e1 - e0) * spb;
+    const uint32_t* entries = uni + (int64_t)grp * union_cap;
+    const int64_t head_base = P.seq_base[b] + (int64_t)j * P.kv_head_stride + chunk * 8;
+    const uint16_t* Kb = K + head_base;
+    const uint16_t* Vb = V + head_base;
+
+    float qf[kG][8], acc[kG][8], m_run[kG], l_run[kG];
+#pragma unroll
+    for (int r = 0; r < kG; ++r) {
+      uint4 raw = *reinterpret_cast<const uint4*>(q + ((int64_t)b * P.n_q_heads + j * kG + r) * kD + chunk * 8);
+      unpack8(raw, qf[r]);
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        qf[r][c] *= q_scale;
+        acc[r][c] = 0.f;
+      }
+      m_run[r] = kNegBig;
+      l_run[r] = 0.f;
+    }
+
+    for (int sl = wave; sl < n_slices; sl += 4) {
+      const int e = e0 + sl / spb, sub = sl % spb;
+      const uint32_t ent = __builtin_amdgcn_readfirstlane(entries[e]);
+      const int blk = (int)(ent >> 8);
+      const uint32_t mask = ent & 255u;
+      const int t0 = blk * geo.g + sub * 16 + tslot;
+      uint4 kraw[kLoads], vraw[kLoads];
+      bool valid[kLoads];
+#pragma unroll
+      for (int i = 0; i < kLoads; ++i) {
+        const int t = t0 + i * kTPL;
+        valid[i] = t < geo.n_tokens;
+        const int64_t row = (int64_t)min(t, geo.n_tokens - 1) * P.token_stride;
+        kraw[i] = *reinterpret_cast<const uint4*>(Kb + row);
+        vraw[i] = *reinterpret_cast<const uint4*>(Vb + row);
+      }
+      float p[kG][kLoads], alpha[kG];
+      {
+        float kf[kLoads][8];
+#pragma unroll
+        for (int i = 0; i < kLoads; ++i) unpack8(kraw[i], kf[i]);
+#pragma unroll
+        for (int r = 0; r < kG; ++r) {
+          if (mask & (1u << r)) {
+            float s[kLoads];
+            float mx = kNegBig;
+#pragma unroll
+            for (int i = 0; i < kLoads; ++i) {
+              float dot = 0.f;
+#pragma unroll
+              for (int c = 0; c < 8; ++c) dot = fmaf(qf[r][c], kf[i][c], dot);
+              dot = group_sum<kLanes>(dot);
+              s[i] = valid[i] ? dot : kNegBig;
+              mx = fmaxf(mx, s[i]);
+            }
+            const float m_new = fmaxf(m_run[r], mx);
+            alpha[r] = __builtin_amdgcn_exp2f(m_run[r] - m_new);
+            float psum = 0.f;
+#pragma unroll
+            for (int i = 0; i < kLoads; ++i) {
+              p[r][i] = valid[i] ? __builtin_amdgcn_exp2f(s[i] - m_new) : 0.f;
+              psum += p[r][i];
+            }
+            l_run[r] = l_run[r] * alpha[r] + psum;
+            m_run[r] = m_new;
+          }
+        }
+      }
+      {
+        float vf[kLoads][8];
+#pragma unroll
+        for (int i = 0; i < kLoads; ++i) unpack8(vraw[i], vf[i]);
+#pragma unroll
+        for (int r = 0; r < kG; ++r) {
+          if (mask & (1u << r)) {
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+              float a = acc[r][c] * alpha[r];
+#pragma unroll
+              for (int i = 0; i < kLoads; ++i) a = fmaf(p[r][i], vf[i][c], a);
+              acc[r][c] = a;
+            }
+          }
+        }
+      }
+    }
+
+    // ---- fuse the token slots of the wave, then the 4 waves, then write the item's partial --------
+#pragma unroll
+    for (int r = 0; r < kG; ++r) {
+      float M = m_run[r];
+#pragma unroll
+      for (int off = kLanes; off < 64; off <<= 1) M = fmaxf(M, __shfl_xor(M, off, kWave));
+      const float w = __builtin_amdgcn_exp2f(m_run[r] - M);
+      float lw = l_run[r] * w;
+#pragma unroll
+      for (int off = kLanes; off < 64; off <<= 1) lw += __shfl_xor(lw, off, kWave);
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        float a = acc[r][c] * w;
+#pragma unroll
+        for (int off = kLanes; off < 64; off <<= 1) a += __shfl_xor(a, off, kWave);
+        acc[r][c] = a;
+      }
+      if (tslot == 0) {
+#pragma unroll
+        for (int c = 0; c < 8; ++c) s_red[wave][r][chunk * 8 + c] = acc[r][c];
+        if (chunk == 0) {
+          s_red[wave][r][kD] = M;
+          s_red[wave][r][kD + 1] = lw;
+        }
+      }
+    }
+    __syncthreads();
+    for (int x = tid; x < kG * kD; x += 256) {
+      const int r = x / kD, c = x % kD;
+      float M = s_red[0][r][kD];
+#pragma unroll
+      for (int w = 1; w < 4; ++w) M = fmaxf(M, s_red[w][r][kD]);
+      float o = 0.f, L = 0.f;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const float sc = __builtin_amdgcn_exp2f(s_red[w][r][kD] - M);
+        o += s_red[w][r][c] * sc;
+        L += s_red[w][r][kD + 1] * sc;
+      }
+      acc_part[((int64_t)item * kG + r) * kD + c] = o;
+      if (c == 0) {
+        ml_part[((int64_t)item * kG + r) * 2] = M;
+        ml_part[((int64_t)item * kG + r) * 2 + 1] = L;
+      }
+    }
+    __syncthreads();
+  }
+}
+
+template <int kD>
+__global__ __launch_bounds__(kD) void merge_kernel(Params P, const int32_t* __restrict__ sched,
+                                                   const float* __restrict__ acc_part,
+                                                   const float* __restrict__ ml_part, float* __restrict__ out,
+                                                   int items_cap) {
+  const int b = blockIdx.y, h = blockIdx.x, c = threadIdx.x;
+  const int G = P.group, j = h / G, r = h % G;
+  const int grp = b * P.n_kv_heads + j;
+  const int p0 = min(sched[grp], items_cap), p1 = min(sched[grp + 1], items_cap);
+  float M = kNegBig;
+  for (int it = p0; it < p1; ++it) M = fmaxf(M, ml_part[((int64_t)it * G + r) * 2]);
+  float o = 0.f, L = 0.f;
+  for (int it = p0; it < p1; ++it) {
+    const float w = __builtin_amdgcn_exp2f(ml_part[((int64_t)it * G + r) * 2] - M);
+    L += ml_part[((int64_t)it * G + r) * 2 + 1] * w;
+    o += acc_part[((int64_t)it * G + r) * kD + c] * w;
+  }
+  out[((int64_t)b * P.n_q_heads + h) * kD + c] = L > 0.f ? o / L : 0.f;
+}
+
+template <int kD, int kG>
+static hipError_t launch_attend(const Params& P, const void* q, const void* K, const void* V, const uint32_t* uni,
+                                const int32_t* ucount, const DecodeWorkspace& W, int32_t* sched, float* acc_part,
+                                float* ml_part, int n_cu, hipStream_t stream) {
+  static int wg_per_cu = 0;  // occupancy of this instantiation, queried once
+  const size_t lds = (size_t)(P.batch * P.n_kv_heads + 1) * sizeof(int);
+  if (wg_per_cu == 0) {
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, attend_kernel<kD, kG>, 256, lds) != hipSuccess || n < 1) n = 1;
+    wg_per_cu = n > 8 ? 8 : n;
+  }
+  int grid = n_cu * wg_per_cu;
+  if (grid > W.items_cap) grid = W.items_cap;
+  hipLaunchKernelGGL((attend_kernel<kD, kG>), dim3(grid), dim3(256), lds, stream, P, (const uint16_t*)q,
+                     (const uint16_t*)K, (const uint16_t*)V, uni, ucount, W.union_cap, sched, acc_part, ml_part,
+                     W.items_cap);
+  return hipGetLastError();
+}
+
+template <int kD>
+static hipError_t dispatch_group(const Params& P, const void* q, const void* K, const void* V, const uint32_t* uni,
+                                 const int32_t* ucount, const DecodeWorkspace& W, int32_t* sched, float* acc_part,
+                                 float* ml_part, int n_cu, hipStream_t stream) {
+  switch (P.group) {
+#define FX_CASE(G) \
+  case G:          \
+    return launch_attend<kD, G>(P, q, K, V, uni, ucount, W, sched, acc_part, ml_part, n_cu, stream);
+    FX_CASE(1) FX_CASE(2) FX_CASE(3) FX_CASE(4) FX_CASE(5) FX_CASE(6) FX_CASE(7) FX_CASE(8)
+#undef FX_CASE
+  }
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_decode(const Params& P, const void* q, const void* K, const void* V, const int32_t* idx,
+                         const int32_t* cnt, float* out, void* workspace, int n_cu, hipStream_t stream) {
+  const DecodeWorkspace W = carve_decode(P);
+  char* ws = static_cast<char*>(workspace);
+  uint32_t* uni = reinterpret_cast<uint32_t*>(ws + W.union_off);
+  int32_t* ucount = reinterpret_cast<int32_t*>(ws + W.ucount_off);
+  int32_t* sched = reinterpret_cast<int32_t*>(ws + W.sched_off);
+  float* acc_part = reinterpret_cast<float*>(ws + W.acc_off);
+  float* ml_part = reinterpret_cast<float*>(ws + W.ml_off);
+
+  const size_t plan_lds = (size_t)((P.nb_stride + 3) / 4) * sizeof(uint32_t);
+  hipLaunchKernelGGL(plan_kernel, dim3(P.n_kv_heads, P.batch), dim3(256), plan_lds, stream, P, idx, cnt, uni, ucount,
+                     W.union_cap);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  e = P.head_dim == 128
+          ? dispatch_group<128>(P, q, K, V, uni, ucount, W, sched, acc_part, ml_part, n_cu, stream)
+          : dispatch_group<64>(P, q, K, V, uni, ucount, W, sched, acc_part, ml_part, n_cu, stream);
+  if (e != hipSuccess) return e;
+  if (P.head_dim == 128)
+    hipLaunchKernelGGL(merge_kernel<128>, dim3(P.n_q_heads, P.batch), dim3(128), 0, stream, P, (const int32_t*)sched,
+                       (const float*)acc_part, (const float*)ml_part, out, W.items_cap);
+  else
+    hipLaunchKernelGGL(merge_kernel<64>, dim3(P.n_q_heads, P.batch), dim3(64), 0, stream, P, (const int32_t*)sched,
+                       (const float*)acc_part, (const float*)ml_part, out, W.items_cap);
+  return hipGetLastError();
+}
+
+}  // namespace fx

@@ -1,0 +1,80 @@
+// Host-side launch entry points of the kernel files and the carving of the caller's workspace.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "fx_device.hpp"
+
+namespace fx {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+// fx_select scratch: one order-preserving 64-bit key per (sequence, query head, block).
+struct SelectWorkspace {
+  size_t keys_off, total;
+};
+inline SelectWorkspace carve_select(const Params& P) {
+  SelectWorkspace W;
+  W.keys_off = 0;
+  W.total = align_up((size_t)P.batch * P.n_q_heads * P.nb_stride * sizeof(uint64_t));
+  return W;
+}
+
+// Split sizing of the decode stage.  A work item is one chunk of one group's union list; the chunk
+// length in tokens is 64 << s with the smallest s in [0, 4] that keeps the item count near kTargetItems.
+constexpr int kMinChunkTokens = 64;
+constexpr int kMaxChunkShift = 4;
+constexpr int kTargetItems = 4096;
+constexpr int kMaxGroups = 4096;
+
+// fx_sparse_decode scratch.
+struct DecodeWorkspace {
+  int32_t union_cap;  // entries per group in the union list
+  int32_t items_cap;  // upper bound on work items
+  size_t union_off;   // uint32 [n_groups][union_cap]   (block << 8) | head mask, ascending by block
+  size_t ucount_off;  // int32  [n_groups]              entries per group
+  size_t sched_off;   // int32  [n_groups + 2]          exclusive item prefix, then total, then chunk tokens
+  size_t acc_off;     // float  [items_cap][group][d]   un-normalised partial outputs
+  size_t ml_off;      // float  [items_cap][group][2]   partial running maximum (log2 domain) and sum
+  size_t total;
+};
+inline DecodeWorkspace carve_decode(const Params& P) {
+  DecodeWorkspace W;
+  const int n_groups = P.batch * P.n_kv_heads;
+  int64_t ucap = 0, tokens_cap_per_seq = 0;
+  for (int j = 0; j < P.n_kv_heads; ++j) {
+    const int64_t g = P.gran[j];
+    const int64_t nb = (P.max_seq_len + g - 1) / g;
+    const int64_t always = (P.sink_tokens + g - 1) / g + (P.window_tokens + g - 1) / g + 1;
+    const int64_t u = nb < always + (int64_t)P.group * P.k_max ? nb : always + (int64_t)P.group * P.k_max;
+    if (u > ucap) ucap = u;
+    tokens_cap_per_seq += u * g;
+  }
+  if (ucap < 1) ucap = 1;
+  const int64_t tokens_cap = tokens_cap_per_seq * P.batch;
+  int64_t items = (tokens_cap + (kMinChunkTokens << kMaxChunkShift) - 1) / (kMinChunkTokens << kMaxChunkShift);
+  if (items < kTargetItems) items = kTargetItems;
+  items += n_groups;
+  W.union_cap = (int32_t)ucap;
+  W.items_cap = (int32_t)items;
+  size_t off = 0;
+  W.union_off = off;  off += align_up((size_t)n_groups * ucap * sizeof(uint32_t));
+  W.ucount_off = off; off += align_up((size_t)n_groups * sizeof(int32_t));
+  W.sched_off = off;  off += align_up((size_t)(n_groups + 2) * sizeof(int32_t));
+  W.acc_off = off;    off += align_up((size_t)items * P.group * P.head_dim * sizeof(float));
+  W.ml_off = off;     off += align_up((size_t)items * P.group * 2 * sizeof(float));
+  W.total = off;
+  return W;
+}
+
+hipError_t launch_summarize(const Params& P, const void* K, void* S, hipStream_t stream);
+hipError_t launch_select(const Params& P, const void* q, const void* S, const float* budget_frac,
+                         const int32_t* budget_blocks, int32_t* idx, int32_t* cnt, void* workspace,
+                         hipStream_t stream);
+hipError_t launch_decode(const Params& P, const void* q, const void* K, const void* V, const int32_t* idx,
+                         const int32_t* cnt, float* out, void* workspace, int n_cu, hipStream_t stream);
+
+}  // namespace fx

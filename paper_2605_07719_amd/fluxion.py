@@ -1,0 +1,187 @@
+"""Python binding of libfluxion.so (the HIP C-ABI library declared in include/fluxion.h).
+
+Argument marshalling only: every step of the path runs in the library's kernels.  PyTorch supplies
+device memory and the current HIP stream.  There is no CPU fallback: if the built library is missing
+or a call fails, this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfluxion.so")
+
+EXPORTS = (
+    "fx_status_string", "fx_summarize", "fx_select_workspace_bytes", "fx_select", "fx_decode_workspace_bytes",
+    "fx_sparse_decode",
+)
+
+FX_OK, FX_ERR_INVALID_ARG, FX_ERR_UNSUPPORTED, FX_ERR_WORKSPACE_TOO_SMALL, FX_ERR_HIP = range(5)
+
+
+class FluxionError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (fx_status {status})")
+
+
+class _CLayout(ctypes.Structure):
+    _fields_ = [
+        ("batch", ctypes.c_int32),
+        ("n_q_heads", ctypes.c_int32),
+        ("n_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32),
+        ("max_seq_len", ctypes.c_int32),
+        ("seq_len", ctypes.c_void_p),
+        ("seq_base", ctypes.c_void_p),
+        ("kv_head_stride", ctypes.c_int64),
+        ("token_stride", ctypes.c_int64),
+        ("sum_base", ctypes.c_void_p),
+        ("gran", ctypes.c_void_p),
+    ]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library.  Raises if it has not been built (run paper_2605_07719_amd/build.py)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2605_07719_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        L.fx_status_string.restype = ctypes.c_char_p
+        L.fx_status_string.argtypes = [ctypes.c_int]
+        L.fx_select_workspace_bytes.restype = ctypes.c_size_t
+        L.fx_select_workspace_bytes.argtypes = [ctypes.c_void_p]
+        L.fx_decode_workspace_bytes.restype = ctypes.c_size_t
+        L.fx_decode_workspace_bytes.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
+        L.fx_summarize.restype = ctypes.c_int
+        L.fx_summarize.argtypes = [ctypes.c_void_p] * 4
+        L.fx_select.restype = ctypes.c_int
+        L.fx_select.argtypes = [ctypes.c_void_p] * 5 + [ctypes.c_int32] * 3 + [ctypes.c_void_p] * 3 + [
+            ctypes.c_size_t, ctypes.c_void_p]
+        L.fx_sparse_decode.restype = ctypes.c_int
+        L.fx_sparse_decode.argtypes = [ctypes.c_void_p] * 6 + [ctypes.c_int32] * 3 + [ctypes.c_void_p] * 2 + [
+            ctypes.c_size_t, ctypes.c_void_p]
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().fx_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != FX_OK:
+        raise FluxionError(status, where)
+
+
+def _dptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+@dataclass
+class Layout:
+    """fx_layout with its device arrays kept alive.  `gran` stays on the host."""
+
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    max_seq_len: int
+    seq_len: torch.Tensor  # int32 [batch], device
+    seq_base: torch.Tensor  # int64 [batch], device
+    kv_head_stride: int
+    token_stride: int
+    sum_base: torch.Tensor  # int64 [batch * n_kv_heads], device
+    gran: np.ndarray  # int32 [n_kv_heads], host
+
+    def __post_init__(self):
+        self.gran = np.ascontiguousarray(self.gran, dtype=np.int32)
+        assert self.seq_len.dtype == torch.int32 and self.seq_base.dtype == torch.int64
+        assert self.sum_base.dtype == torch.int64
+
+    @property
+    def batch(self) -> int:
+        return int(self.seq_len.numel())
+
+    def c_struct(self) -> _CLayout:
+        return _CLayout(
+            self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.max_seq_len,
+            self.seq_len.data_ptr(), self.seq_base.data_ptr(), self.kv_head_stride, self.token_stride,
+            self.sum_base.data_ptr(), self.gran.ctypes.data,
+        )
+
+    @staticmethod
+    def from_host(n_q_heads, n_kv_heads, head_dim, seq_len: Sequence[int], seq_base: Sequence[int],
+                  kv_head_stride: int, token_stride: int, sum_base: Sequence[int], gran: Sequence[int],
+                  device="cuda", max_seq_len: Optional[int] = None) -> "Layout":
+        seq_len = np.asarray(seq_len, dtype=np.int32)
+        return Layout(
+            n_q_heads=n_q_heads, n_kv_heads=n_kv_heads, head_dim=head_dim,
+            max_seq_len=int(seq_len.max()) if max_seq_len is None else int(max_seq_len),
+            seq_len=torch.from_numpy(seq_len).to(device),
+            seq_base=torch.from_numpy(np.asarray(seq_base, dtype=np.int64)).to(device),
+            kv_head_stride=int(kv_head_stride), token_stride=int(token_stride),
+            sum_base=torch.from_numpy(np.asarray(sum_base, dtype=np.int64).reshape(-1)).to(device),
+            gran=np.asarray(gran, dtype=np.int32),
+        )
+
+
+def select_workspace_bytes(layout: Layout) -> int:
+    c = layout.c_struct()
+    return int(lib().fx_select_workspace_bytes(ctypes.byref(c)))
+
+
+def decode_workspace_bytes(layout: Layout, k_max: int, sink_tokens: int, window_tokens: int) -> int:
+    c = layout.c_struct()
+    return int(lib().fx_decode_workspace_bytes(ctypes.byref(c), k_max, sink_tokens, window_tokens))
+
+
+def summarize(layout: Layout, K: torch.Tensor, summaries: torch.Tensor, stream=None) -> None:
+    """fx_summarize: per-block min/max rows of K into `summaries` (bf16 [total_blocks, 2, d])."""
+    c = layout.c_struct()
+    _check(lib().fx_summarize(ctypes.byref(c), _dptr(K), _dptr(summaries), _stream(stream)), "fx_summarize")
+
+
+def select(layout: Layout, q: torch.Tensor, summaries: torch.Tensor, *, budget_frac: Optional[torch.Tensor] = None,
+           budget_blocks: Optional[torch.Tensor] = None, sink_tokens: int, window_tokens: int, k_max: int,
+           idx: torch.Tensor, cnt: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:
+    """fx_select: block scores and per-head top-k into idx (int32 [batch,Hq,k_max]) and cnt (int32 [batch,Hq])."""
+    c = layout.c_struct()
+    _check(
+        lib().fx_select(
+            ctypes.byref(c), _dptr(q), _dptr(summaries), _dptr(budget_frac), _dptr(budget_blocks), sink_tokens,
+            window_tokens, k_max, _dptr(idx), _dptr(cnt), _dptr(workspace),
+            workspace.numel() * workspace.element_size(), _stream(stream),
+        ),
+        "fx_select",
+    )
+
+
+def sparse_decode(layout: Layout, q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, idx: torch.Tensor,
+                  cnt: torch.Tensor, *, k_max: int, sink_tokens: int, window_tokens: int, out: torch.Tensor,
+                  workspace: torch.Tensor, stream=None) -> None:
+    """fx_sparse_decode: split-K sparse attention + merge into out (float32 [batch,Hq,d])."""
+    c = layout.c_struct()
+    _check(
+        lib().fx_sparse_decode(
+            ctypes.byref(c), _dptr(q), _dptr(K), _dptr(V), _dptr(idx), _dptr(cnt), k_max, sink_tokens,
+            window_tokens, _dptr(out), _dptr(workspace), workspace.numel() * workspace.element_size(),
+            _stream(stream),
+        ),
+        "fx_sparse_decode",
+    )

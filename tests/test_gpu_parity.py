@@ -1,0 +1,217 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs.
+
+Bar: summaries equal element by element; selected block sets bit-exact (near-tie rule of
+helpers.compare_selection); attention outputs within 5e-3 max abs error."""
+import numpy as np
+import pytest
+import torch
+
+from helpers import GpuProblem, bf16_bits_to_f64, compare_selection, host_arrays, oracle_layout
+from oracle import fx_oracle as O
+from paper_2605_07719_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+TOL = 5e-3
+THREADS = O.default_threads()
+
+
+def small_cases():
+    """Sizes the oracle finishes in seconds that still span several tiles and ragged tails."""
+    return {
+        "tiny": W.tiny(),
+        "d64_ragged_mixed_gran": W.Workload(
+            name="a", n_q_heads=8, n_kv_heads=2, head_dim=64, seq_len=[3000, 1111, 4097, 50], gran=[16, 48],
+            sink_tokens=64, window_tokens=256, budget_frac=np.full((4, 8), 0.1, dtype=np.float32), seed=1),
+        "d128_g4": W.Workload(
+            name="b", n_q_heads=8, n_kv_heads=2, head_dim=128, seq_len=[5000, 2049], gran=[32, 64],
+            sink_tokens=32, window_tokens=256, budget_frac=np.full((2, 8), 0.07, dtype=np.float32),
+            outlier_channels=4, q_mode="near_key", seed=2),
+        "d128_g7_ragged": W.Workload(
+            name="c", n_q_heads=14, n_kv_heads=2, head_dim=128, seq_len=[4000, 777, 2500], gran=[32, 32],
+            sink_tokens=64, window_tokens=256, budget_frac=W._head_budgets(14, 2, 0.05, 0.01, 0.2,
+                                                                           np.random.default_rng(5))[None].repeat(3, 0),
+            planted_density=0.02, seed=3),
+        "d128_g8_gran128": W.Workload(
+            name="d", n_q_heads=8, n_kv_heads=1, head_dim=128, seq_len=[6000], gran=[128],
+            sink_tokens=64, window_tokens=256, budget_frac=np.full((1, 8), 0.2, dtype=np.float32), seed=4),
+        "mha_g1": W.Workload(
+            name="e", n_q_heads=3, n_kv_heads=3, head_dim=128, seq_len=[1500, 900], gran=[16, 32, 80],
+            sink_tokens=64, window_tokens=256, budget_frac=np.full((2, 3), 0.15, dtype=np.float32), seed=5),
+    }
+
+
+def run_oracle(wl, t):
+    L = oracle_layout(wl)
+    q, K, V = host_arrays(t)
+    S = O.summarize(L, K, threads=THREADS)
+    kmax = max(1, L.max_blocks())
+    idx, cnt, gap, kth = O.select(L, q, S, budget_frac=wl.budget_frac, budget_blocks=wl.budget_blocks,
+                                  sink_tokens=wl.sink_tokens, window_tokens=wl.window_tokens, k_max=kmax,
+                                  threads=THREADS)
+    sc = O.scores(L, q, S, wl.sink_tokens, wl.window_tokens, threads=THREADS)
+    out = O.sparse_attention(L, q, K, V, idx, cnt, sink_tokens=wl.sink_tokens, window_tokens=wl.window_tokens,
+                             threads=THREADS)
+    return dict(L=L, q=q, K=K, V=V, S=S, idx=idx, cnt=cnt, gap=gap, kth=kth, scores=sc, out=out, k_max=kmax)
+
+
+@pytest.mark.parametrize("name", list(small_cases().keys()))
+def test_three_stages_against_oracle(name):
+    wl = small_cases()[name]
+    t = W.make_layer(wl)
+    ref = run_oracle(wl, t)
+    print(f"case={name} seed={wl.seed} seq_len={wl.seq_len} gran={wl.gran}", flush=True)
+    gp = GpuProblem(wl, t, k_max=ref["k_max"])
+
+    # stage 1: summaries, element by element (as values: +-0 compare equal)
+    S = gp.summarize()
+    torch.cuda.synchronize()
+    S_gpu = bf16_bits_to_f64(W.to_u16(S))
+    assert np.array_equal(S_gpu, bf16_bits_to_f64(ref["S"]))
+
+    # stage 2: selection, index-exact
+    idx, cnt = gp.select()
+    torch.cuda.synchronize()
+    exempt, differ = compare_selection(idx.cpu().numpy(), cnt.cpu().numpy(), ref["idx"], ref["cnt"], ref["gap"],
+                                       ref["kth"], ref["scores"], None)
+    print(f"  near-tie heads {exempt}, heads differing inside the band {differ}", flush=True)
+
+    # stage 3: attention on the oracle's indices (decoupled from stage 2), then on the GPU's own
+    out = gp.decode(ref["idx"], ref["cnt"]).cpu().numpy().astype(np.float64)
+    err = np.abs(out - ref["out"]).max()
+    print(f"  max abs err (oracle indices) {err:.3e}", flush=True)
+    assert err < TOL
+    gp.select()
+    out2 = gp.decode().cpu().numpy().astype(np.float64)
+    if differ == 0:
+        assert np.abs(out2 - ref["out"]).max() < TOL
+
+
+def test_budget_one_is_dense_and_budget_zero_is_streaming():
+    wl = small_cases()["d128_g4"]
+    t = W.make_layer(wl)
+    L = oracle_layout(wl)
+    q, K, V = host_arrays(t)
+    gp = GpuProblem(wl, t)
+    gp.summarize()
+    gp.select(budget_frac=1.0)
+    out = gp.decode().cpu().numpy().astype(np.float64)
+    dense = O.dense_attention(L, q, K, V, threads=THREADS)
+    assert np.abs(out - dense).max() < TOL
+    gp.select(budget_frac=0.0)
+    assert int(gp.cnt.abs().sum()) == 0 and bool((gp.idx == -1).all())
+    out0 = gp.decode().cpu().numpy().astype(np.float64)
+    none = O.sparse_attention(L, q, K, V, -np.ones((wl.batch, wl.n_q_heads, 1), np.int32),
+                              np.zeros((wl.batch, wl.n_q_heads), np.int32), sink_tokens=wl.sink_tokens,
+                              window_tokens=wl.window_tokens, threads=THREADS)
+    assert np.abs(out0 - none).max() < TOL
+
+
+def test_exact_ties_and_integer_budgets():
+    """Duplicated blocks score identically; the lower indices must win on the GPU as in the oracle."""
+    wl = W.Workload(name="ties", n_q_heads=4, n_kv_heads=1, head_dim=128, seq_len=[4096], gran=[16],
+                    sink_tokens=16, window_tokens=64, seed=9)
+    t = W.make_layer(wl)
+    for src, dst in ((10, 40), (10, 77), (11, 200), (150, 151)):
+        t.K[0, dst * 16 : dst * 16 + 16] = t.K[0, src * 16 : src * 16 + 16]
+    # make the duplicated blocks strong candidates for head 0
+    t.K[0, 160:176] += (4.0 * t.q[0, 0].float().sign()).to(torch.bfloat16)
+    for dst in (40, 77):
+        t.K[0, dst * 16 : dst * 16 + 16] = t.K[0, 160:176]
+    L = oracle_layout(wl)
+    q, K, V = host_arrays(t)
+    S = O.summarize(L, K)
+    sc = O.scores(L, q, S, 16, 64)
+    gp = GpuProblem(wl, t, k_max=64)
+    gp.summarize()
+    for k in (1, 2, 3, 5, 33, 64):
+        bud = np.full((1, 4), k, dtype=np.int32)
+        idx_o, cnt_o, gap, kth = O.select(L, q, S, budget_blocks=bud, sink_tokens=16, window_tokens=64, k_max=64)
+        idx, cnt = gp.select(budget_blocks=bud)
+        compare_selection(idx.cpu().numpy(), cnt.cpu().numpy(), idx_o, cnt_o, gap, kth, sc, None)
+    idx_o, _, gap, _ = O.select(L, q, S, budget_blocks=np.full((1, 4), 2, np.int32), sink_tokens=16, window_tokens=64,
+                                k_max=64)
+    assert idx_o[0, 0, :2].tolist() == [10, 40] and gap[0, 0] == 0.0
+    gp.select(budget_blocks=np.full((1, 4), 2, np.int32))
+    assert gp.idx[0, 0, :2].tolist() == [10, 40]
+
+
+def test_short_and_degenerate_sequences():
+    """Contexts shorter than sink + window (no candidates), a one-token sequence, a partial tail block."""
+    wl = W.Workload(name="short", n_q_heads=4, n_kv_heads=2, head_dim=128, seq_len=[1, 17, 300, 321, 64],
+                    gran=[16, 32], sink_tokens=64, window_tokens=256,
+                    budget_frac=np.full((5, 4), 0.5, dtype=np.float32), seed=11)
+    t = W.make_layer(wl)
+    ref = run_oracle(wl, t)
+    gp = GpuProblem(wl, t, k_max=ref["k_max"])
+    gp.summarize()
+    assert np.array_equal(bf16_bits_to_f64(W.to_u16(gp.S)), bf16_bits_to_f64(ref["S"]))
+    idx, cnt = gp.select()
+    compare_selection(idx.cpu().numpy(), cnt.cpu().numpy(), ref["idx"], ref["cnt"], ref["gap"], ref["kth"],
+                      ref["scores"], None)
+    out = gp.decode().cpu().numpy().astype(np.float64)
+    assert np.abs(out - ref["out"]).max() < TOL
+    dense = O.dense_attention(ref["L"], ref["q"], ref["K"], ref["V"])
+    assert np.abs(out[:2] - dense[:2]).max() < TOL  # no candidates: dense over all valid tokens
+
+
+def test_decode_accepts_arbitrary_index_lists():
+    """Unsorted, duplicated, out-of-range and sink/window-overlapping entries: ignored or harmless."""
+    wl = small_cases()["d128_g7_ragged"]
+    wl.seq_len[1] = 1777
+    t = W.make_layer(wl)
+    L = oracle_layout(wl)
+    q, K, V = host_arrays(t)
+    rng = np.random.default_rng(0)
+    kmax = 40
+    idx = -np.ones((wl.batch, wl.n_q_heads, kmax), np.int32)
+    cnt = np.zeros((wl.batch, wl.n_q_heads), np.int32)
+    clean = -np.ones_like(idx)
+    for b in range(wl.batch):
+        for h in range(wl.n_q_heads):
+            nb = L.n_blocks(b, h // wl.group)
+            good = rng.choice(np.arange(3, nb - 10), size=20, replace=False)
+            junk = np.array([-5, nb, nb + 100, 0, nb - 1, good[0], good[1]], dtype=np.int64)
+            lst = rng.permutation(np.concatenate([good, junk]))
+            idx[b, h, : lst.size] = lst
+            cnt[b, h] = lst.size
+            clean[b, h, :20] = np.sort(good)
+    gp = GpuProblem(wl, t, k_max=kmax)
+    out = gp.decode(idx, cnt).cpu().numpy().astype(np.float64)
+    ref = O.sparse_attention(L, q, K, V, clean, np.full_like(cnt, 20), sink_tokens=wl.sink_tokens,
+                             window_tokens=wl.window_tokens, threads=THREADS)
+    assert np.abs(out - ref).max() < TOL
+
+
+def test_token_major_layout():
+    """K/V stored [token][kv_head][d]: same results through different strides."""
+    wl = small_cases()["d128_g4"]
+    t = W.make_layer(wl)
+    ref = run_oracle(wl, t)
+    gp = GpuProblem(wl, t, k_max=ref["k_max"])
+    Hkv, T, d = t.K.shape
+    pl = W.placement(wl)
+    gp.K = t.K.permute(1, 0, 2).contiguous().cuda()
+    gp.V = t.V.permute(1, 0, 2).contiguous().cuda()
+    gp.layout = gp.F.Layout.from_host(wl.n_q_heads, Hkv, d, pl.seq_len, pl.tok_off * Hkv * d, d, Hkv * d,
+                                      pl.sum_base.reshape(-1), pl.gran)
+    gp.summarize()
+    assert np.array_equal(bf16_bits_to_f64(W.to_u16(gp.S)), bf16_bits_to_f64(ref["S"]))
+    idx, cnt = gp.select()
+    compare_selection(idx.cpu().numpy(), cnt.cpu().numpy(), ref["idx"], ref["cnt"], ref["gap"], ref["kth"],
+                      ref["scores"], None)
+    out = gp.decode().cpu().numpy().astype(np.float64)
+    assert np.abs(out - ref["out"]).max() < TOL
+
+
+def test_runs_are_reproducible():
+    wl = small_cases()["d128_g7_ragged"]
+    t = W.make_layer(wl)
+    gp = GpuProblem(wl, t)
+    gp.summarize()
+    gp.select()
+    a = gp.decode().clone()
+    for _ in range(3):
+        gp.select()
+        b = gp.decode()
+        assert torch.equal(a, b)
