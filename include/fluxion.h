@@ -53,7 +53,7 @@ const char* fx_status_string(fx_status status);
  *     S[((sum_base[b * n_kv_heads + j] + i) * 2 + 0) * head_dim + c]   (minimum)
  *     S[((sum_base[b * n_kv_heads + j] + i) * 2 + 1) * head_dim + c]   (maximum).
  * Supported: head_dim 64 or 128; n_q_heads a multiple of n_kv_heads with group size <= 8;
- * n_kv_heads <= 64; gran[j] a multiple of 16 in [16, 128]; max_seq_len <= 2^20.
+ * n_kv_heads <= 64; gran[j] a multiple of 16 in [16, 128]; max_seq_len <= 2^19; batch * n_kv_heads <= 4096.
  * Alignment: K, V, S and q 16-byte aligned; token_stride, kv_head_stride and every seq_base[b]
  * multiples of 8 elements; token_stride >= head_dim.
  */
@@ -130,6 +130,17 @@ size_t fx_decode_workspace_bytes(const fx_layout* layout, int32_t k_max, int32_t
 fx_status fx_sparse_decode(const fx_layout* layout, const void* q, const void* K, const void* V, const int32_t* idx,
                            const int32_t* cnt, int32_t k_max, int32_t sink_tokens, int32_t window_tokens, float* out,
                            void* workspace, size_t workspace_bytes, void* stream);
+
+/* Measurement aid (not part of the method).  While enabled, fx_select and fx_sparse_decode bracket every
+ * kernel they launch with HIP events recorded on the caller's stream; fx_profile_read waits for the
+ * events of the most recent call of each and returns the kernel durations in milliseconds:
+ *   ms[0] block scoring, ms[1] top-k, ms[2] union-list planning, ms[3] split-K attention, ms[4] merge.
+ * Enabling creates the events (the only place the library creates HIP objects); disabling destroys
+ * them.  Entries of kernels that have not run since enabling are -1.  `n` must be 5.
+ * Not thread-safe; meant for benchmarks.  Errors: INVALID_ARG, HIP. */
+#define FX_PROFILE_SLOTS 5
+fx_status fx_profile_enable(int enable);
+fx_status fx_profile_read(float* ms, int n);
 
 #ifdef __cplusplus
 }

@@ -64,7 +64,46 @@ int compute_units() {
 
 }  // namespace
 
+namespace fx {
+Profiler& profiler() {
+  static Profiler p;
+  return p;
+}
+}  // namespace fx
+
 extern "C" {
+
+fx_status fx_profile_enable(int enable) {
+  fx::Profiler& p = fx::profiler();
+  if ((enable != 0) == p.enabled) return FX_OK;
+  if (enable) {
+    for (int s = 0; s < fx::kNumSlots; ++s) {
+      if (hipEventCreate(&p.start[s]) != hipSuccess || hipEventCreate(&p.stop[s]) != hipSuccess) return FX_ERR_HIP;
+      p.recorded[s] = false;
+    }
+    p.enabled = true;
+  } else {
+    p.enabled = false;
+    for (int s = 0; s < fx::kNumSlots; ++s) {
+      (void)hipEventDestroy(p.start[s]);
+      (void)hipEventDestroy(p.stop[s]);
+      p.recorded[s] = false;
+    }
+  }
+  return FX_OK;
+}
+
+fx_status fx_profile_read(float* ms, int n) {
+  fx::Profiler& p = fx::profiler();
+  if (!ms || n != fx::kNumSlots || !p.enabled) return FX_ERR_INVALID_ARG;
+  for (int s = 0; s < fx::kNumSlots; ++s) {
+    ms[s] = -1.f;
+    if (!p.recorded[s]) continue;
+    if (hipEventSynchronize(p.stop[s]) != hipSuccess) return FX_ERR_HIP;
+    if (hipEventElapsedTime(&ms[s], p.start[s], p.stop[s]) != hipSuccess) return FX_ERR_HIP;
+  }
+  return FX_OK;
+}
 
 const char* fx_status_string(fx_status status) {
   switch (status) {

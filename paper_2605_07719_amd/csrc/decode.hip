@@ -333,14 +333,21 @@ hipError_t launch_decode(const Params& P, const void* q, const void* K, const vo
   float* ml_part = reinterpret_cast<float*>(ws + W.ml_off);
 
   const size_t plan_lds = (size_t)((P.nb_stride + 3) / 4) * sizeof(uint32_t);
-  hipLaunchKernelGGL(plan_kernel, dim3(P.n_kv_heads, P.batch), dim3(256), plan_lds, stream, P, idx, cnt, uni, ucount,
-                     W.union_cap);
+  {
+    ScopedSlot prof(kSlotPlan, stream);
+    hipLaunchKernelGGL(plan_kernel, dim3(P.n_kv_heads, P.batch), dim3(256), plan_lds, stream, P, idx, cnt, uni,
+                       ucount, W.union_cap);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  e = P.head_dim == 128
-          ? dispatch_group<128>(P, q, K, V, uni, ucount, W, sched, acc_part, ml_part, n_cu, stream)
-          : dispatch_group<64>(P, q, K, V, uni, ucount, W, sched, acc_part, ml_part, n_cu, stream);
+  {
+    ScopedSlot prof(kSlotAttend, stream);
+    e = P.head_dim == 128
+            ? dispatch_group<128>(P, q, K, V, uni, ucount, W, sched, acc_part, ml_part, n_cu, stream)
+            : dispatch_group<64>(P, q, K, V, uni, ucount, W, sched, acc_part, ml_part, n_cu, stream);
+  }
   if (e != hipSuccess) return e;
+  ScopedSlot prof(kSlotMerge, stream);
   if (P.head_dim == 128)
     hipLaunchKernelGGL(merge_kernel<128>, dim3(P.n_q_heads, P.batch), dim3(128), 0, stream, P, (const int32_t*)sched,
                        (const float*)acc_part, (const float*)ml_part, out, W.items_cap);

@@ -70,6 +70,28 @@ inline DecodeWorkspace carve_decode(const Params& P) {
   return W;
 }
 
+// Optional per-kernel timing (benchmarks only): slots are recorded around launches when enabled.
+enum ProfileSlot { kSlotScore = 0, kSlotTopk = 1, kSlotPlan = 2, kSlotAttend = 3, kSlotMerge = 4, kNumSlots = 5 };
+struct Profiler {
+  bool enabled = false;
+  hipEvent_t start[kNumSlots] = {}, stop[kNumSlots] = {};
+  bool recorded[kNumSlots] = {};
+};
+Profiler& profiler();
+struct ScopedSlot {  // records start on construction and stop on destruction, on `stream`
+  int slot;
+  hipStream_t stream;
+  ScopedSlot(int s, hipStream_t st) : slot(s), stream(st) {
+    if (profiler().enabled) (void)hipEventRecord(profiler().start[slot], stream);
+  }
+  ~ScopedSlot() {
+    if (profiler().enabled) {
+      (void)hipEventRecord(profiler().stop[slot], stream);
+      profiler().recorded[slot] = true;
+    }
+  }
+};
+
 hipError_t launch_summarize(const Params& P, const void* K, void* S, hipStream_t stream);
 hipError_t launch_select(const Params& P, const void* q, const void* S, const float* budget_frac,
                          const int32_t* budget_blocks, int32_t* idx, int32_t* cnt, void* workspace,

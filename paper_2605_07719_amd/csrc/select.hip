@@ -203,14 +203,18 @@ hipError_t launch_select(const Params& P, const void* q, const void* S, const fl
   const int lanes = P.head_dim / 8;
   const int tile = (256 / lanes) * 4;
   dim3 sgrid((P.nb_stride + tile - 1) / tile, P.n_kv_heads * n_pass, P.batch);
+  {
+  ScopedSlot prof(kSlotScore, stream);
   if (P.head_dim == 128)
     hipLaunchKernelGGL((score_kernel<128, kHP>), sgrid, dim3(256), 0, stream, P, (const uint16_t*)q,
                        (const uint16_t*)S, keys);
   else
     hipLaunchKernelGGL((score_kernel<64, kHP>), sgrid, dim3(256), 0, stream, P, (const uint16_t*)q,
                        (const uint16_t*)S, keys);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  ScopedSlot prof(kSlotTopk, stream);
   hipLaunchKernelGGL(topk_kernel, dim3(P.n_q_heads, P.batch), dim3(256), 0, stream, P, (const uint64_t*)keys,
                      budget_frac, budget_blocks, idx, cnt);
   return hipGetLastError();

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libfluxion.so")
 
 EXPORTS = (
     "fx_status_string", "fx_summarize", "fx_select_workspace_bytes", "fx_select", "fx_decode_workspace_bytes",
-    "fx_sparse_decode",
+    "fx_sparse_decode", "fx_profile_enable", "fx_profile_read",
 )
 
 FX_OK, FX_ERR_INVALID_ARG, FX_ERR_UNSUPPORTED, FX_ERR_WORKSPACE_TOO_SMALL, FX_ERR_HIP = range(5)
@@ -71,6 +71,10 @@ def lib() -> ctypes.CDLL:
         L.fx_sparse_decode.restype = ctypes.c_int
         L.fx_sparse_decode.argtypes = [ctypes.c_void_p] * 6 + [ctypes.c_int32] * 3 + [ctypes.c_void_p] * 2 + [
             ctypes.c_size_t, ctypes.c_void_p]
+        L.fx_profile_enable.restype = ctypes.c_int
+        L.fx_profile_enable.argtypes = [ctypes.c_int]
+        L.fx_profile_read.restype = ctypes.c_int
+        L.fx_profile_read.argtypes = [ctypes.c_void_p, ctypes.c_int]
         _lib = L
     return _lib
 
@@ -185,3 +189,18 @@ def sparse_decode(layout: Layout, q: torch.Tensor, K: torch.Tensor, V: torch.Ten
         ),
         "fx_sparse_decode",
     )
+
+
+PROFILE_SLOTS = ("score", "topk", "plan", "attend", "merge")
+
+
+def profile_enable(enable: bool) -> None:
+    """fx_profile_enable: bracket every kernel of fx_select / fx_sparse_decode with HIP events."""
+    _check(lib().fx_profile_enable(1 if enable else 0), "fx_profile_enable")
+
+
+def profile_read() -> dict:
+    """fx_profile_read: milliseconds per kernel of the most recent calls (waits for them)."""
+    ms = (ctypes.c_float * len(PROFILE_SLOTS))()
+    _check(lib().fx_profile_read(ms, len(PROFILE_SLOTS)), "fx_profile_read")
+    return {name: float(ms[i]) for i, name in enumerate(PROFILE_SLOTS)}
