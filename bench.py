@@ -193,6 +193,35 @@ def measure(ls: LayerSet, steps: int, warmup: int, use_graph: bool) -> dict:
     }
 
 
+def stream_probe(n_bytes=4 << 30) -> dict:
+    """Plain streaming read and plain copy of a buffer far larger than the caches: what this machine reaches
+    with no arithmetic at all (context for the roofline fraction, and the known-size transfers that
+    hardware-counter readings are scaled against)."""
+    import torch
+
+    from paper_2605_07719_amd import fluxion as F
+
+    src = torch.empty(n_bytes, dtype=torch.uint8, device="cuda").random_(0, 255)
+    dst = torch.empty(n_bytes, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(fn, reps=5):
+        fn()
+        torch.cuda.synchronize()
+        ev0.record()
+        for _ in range(reps):
+            fn()
+        ev1.record()
+        torch.cuda.synchronize()
+        return ev0.elapsed_time(ev1) / reps
+
+    read = {w: n_bytes / timed(lambda: F.probe_read(src, sink, w)) / 1e6 for w in (1, 2, 8)}
+    copy_ms = timed(lambda: F.probe_copy(dst, src, 4))
+    return {"bytes": n_bytes, "read_GBps": max(read.values()), "read_GBps_by_wg_per_cu": read,
+            "copy_GBps_read_plus_write": 2 * n_bytes / copy_ms / 1e6}
+
+
 def cpu_baseline(wl, seconds=12.0) -> dict:
     """The oracle, as it stands, on this machine's host cores: selection + sparse attention of one layer-step."""
     import torch
@@ -278,6 +307,12 @@ def main():
             del ls
             torch.cuda.empty_cache()
 
+    probe = stream_probe()
+    log("[bench] stream probe:", json.dumps(probe))
+    head["attend_frac_of_stream_read"] = head["attend_GBps"] / probe["read_GBps"]
+    for r in others:
+        r["attend_frac_of_stream_read"] = r["attend_GBps"] / probe["read_GBps"]
+
     base = None
     if not args.no_cpu_baseline:
         base = cpu_baseline(head_wl)
@@ -312,6 +347,7 @@ def main():
             "frac": head["attend_frac_of_hbm_peak"], "traffic": None,
             "bytes_per_launch": head["decode_unique_bytes"], "us_per_launch": head["kernel_us"]["attend"],
         },
+        "stream_probe": probe,
         "workloads": others,
         "cpu_baseline": base,
     }

@@ -142,6 +142,14 @@ fx_status fx_sparse_decode(const fx_layout* layout, const void* q, const void* K
 fx_status fx_profile_enable(int enable);
 fx_status fx_profile_read(float* ms, int n);
 
+/* Measurement aids (not part of the method): a plain streaming read of `bytes` bytes at `src`
+ * (nothing is written unless a data-dependent check that practically never holds fires; `sink` must
+ * point to at least 4 writable bytes) and a plain copy.  Both run `wg_per_cu` (1..32) persistent
+ * workgroups per compute unit with 16-byte loads.  `bytes` is rounded down to a multiple of 16.
+ * Errors: INVALID_ARG (null, misaligned, bytes < 16), HIP. */
+fx_status fx_probe_read(const void* src, size_t bytes, void* sink, int wg_per_cu, void* stream);
+fx_status fx_probe_copy(void* dst, const void* src, size_t bytes, int wg_per_cu, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

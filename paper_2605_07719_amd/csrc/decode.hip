@@ -75,6 +75,7 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
   __shared__ float s_red[4][kG][kD + 2];
   __shared__ int s_scan[4];
   __shared__ unsigned long long s_total;
+  __shared__ uint32_t s_ent[kMaxChunkEntries];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int chunk = lane % kLanes, tslot = lane / kLanes;
@@ -139,82 +140,101 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
     const uint16_t* Kb = K + head_base;
     const uint16_t* Vb = V + head_base;
 
-    float qf[kG][8], acc[kG][8], m_run[kG], l_run[kG];
+    // the item's union entries go to LDS once, so the per-slice address chain starts from LDS
+    if (tid < e1 - e0) s_ent[tid] = entries[e0 + tid];
+    __syncthreads();
+
+    // q stays packed (2 bf16 per register); the 1/sqrt(D) and log2(e) factors are applied to the dot product
+    uint4 qp[kG];
+    float acc[kG][8], m_run[kG], l_run[kG];
 #pragma unroll
     for (int r = 0; r < kG; ++r) {
-      uint4 raw = *reinterpret_cast<const uint4*>(q + ((int64_t)b * P.n_q_heads + j * kG + r) * kD + chunk * 8);
-      unpack8(raw, qf[r]);
+      qp[r] = *reinterpret_cast<const uint4*>(q + ((int64_t)b * P.n_q_heads + j * kG + r) * kD + chunk * 8);
 #pragma unroll
-      for (int c = 0; c < 8; ++c) {
-        qf[r][c] *= q_scale;
-        acc[r][c] = 0.f;
-      }
+      for (int c = 0; c < 8; ++c) acc[r][c] = 0.f;
       m_run[r] = kNegBig;
       l_run[r] = 0.f;
     }
 
-    for (int sl = wave; sl < n_slices; sl += 4) {
-      const int e = e0 + sl / spb, sub = sl % spb;
-      const uint32_t ent = __builtin_amdgcn_readfirstlane(entries[e]);
-      const int blk = (int)(ent >> 8);
-      const uint32_t mask = ent & 255u;
-      const int t0 = blk * geo.g + sub * 16 + tslot;
-      uint4 kraw[kLoads], vraw[kLoads];
-      bool valid[kLoads];
+    // Software pipeline: the K/V rows of the wave's next slice are requested before the current
+    // slice is consumed, so every wave always has one slice (8 KiB at d = 128) in flight.
+    uint4 kraw[kLoads], vraw[kLoads], knext[kLoads], vnext[kLoads];
+    uint32_t mask_next = 0;
+    int t0_next = 0;
+    auto issue = [&](int sl, uint4* kr, uint4* vr, uint32_t& mask_out, int& t0_out) {
+      const uint32_t ent = __builtin_amdgcn_readfirstlane(s_ent[sl / spb]);
+      mask_out = ent & 255u;
+      t0_out = (int)(ent >> 8) * geo.g + (sl % spb) * 16 + tslot;
 #pragma unroll
       for (int i = 0; i < kLoads; ++i) {
-        const int t = t0 + i * kTPL;
-        valid[i] = t < geo.n_tokens;
-        const int64_t row = (int64_t)min(t, geo.n_tokens - 1) * P.token_stride;
-        kraw[i] = *reinterpret_cast<const uint4*>(Kb + row);
-        vraw[i] = *reinterpret_cast<const uint4*>(Vb + row);
+        const int64_t row = (int64_t)min(t0_out + i * kTPL, geo.n_tokens - 1) * P.token_stride;
+        kr[i] = *reinterpret_cast<const uint4*>(Kb + row);
+        vr[i] = *reinterpret_cast<const uint4*>(Vb + row);
       }
-      float p[kG][kLoads], alpha[kG];
-      {
-        float kf[kLoads][8];
+    };
+    if (wave < n_slices) issue(wave, knext, vnext, mask_next, t0_next);
+
+    for (int sl = wave; sl < n_slices; sl += 4) {
+      const uint32_t mask = mask_next;
+      const int t0 = t0_next;
 #pragma unroll
-        for (int i = 0; i < kLoads; ++i) unpack8(kraw[i], kf[i]);
+      for (int i = 0; i < kLoads; ++i) {
+        kraw[i] = knext[i];
+        vraw[i] = vnext[i];
+      }
+      if (sl + 4 < n_slices) issue(sl + 4, knext, vnext, mask_next, t0_next);
+
+      // logits (log2 domain) of the slice's tokens for every head that wants this block
+      float sp[kG][kLoads];
+#pragma unroll
+      for (int i = 0; i < kLoads; ++i) {
+        const bool valid = t0 + i * kTPL < geo.n_tokens;
 #pragma unroll
         for (int r = 0; r < kG; ++r) {
           if (mask & (1u << r)) {
-            float s[kLoads];
-            float mx = kNegBig;
-#pragma unroll
-            for (int i = 0; i < kLoads; ++i) {
-              float dot = 0.f;
-#pragma unroll
-              for (int c = 0; c < 8; ++c) dot = fmaf(qf[r][c], kf[i][c], dot);
-              dot = group_sum<kLanes>(dot);
-              s[i] = valid[i] ? dot : kNegBig;
-              mx = fmaxf(mx, s[i]);
-            }
-            const float m_new = fmaxf(m_run[r], mx);
-            alpha[r] = __builtin_amdgcn_exp2f(m_run[r] - m_new);
-            float psum = 0.f;
-#pragma unroll
-            for (int i = 0; i < kLoads; ++i) {
-              p[r][i] = valid[i] ? __builtin_amdgcn_exp2f(s[i] - m_new) : 0.f;
-              psum += p[r][i];
-            }
-            l_run[r] = l_run[r] * alpha[r] + psum;
-            m_run[r] = m_new;
+            float dot = dot2_bf16(qp[r].x, kraw[i].x, 0.f);
+            dot = dot2_bf16(qp[r].y, kraw[i].y, dot);
+            dot = dot2_bf16(qp[r].z, kraw[i].z, dot);
+            dot = dot2_bf16(qp[r].w, kraw[i].w, dot);
+            dot = group_sum<kLanes>(dot) * q_scale;
+            sp[r][i] = valid ? dot : kNegBig;
           }
         }
       }
-      {
-        float vf[kLoads][8];
+      // online-softmax update per head: new maximum, rescale, probabilities
 #pragma unroll
-        for (int i = 0; i < kLoads; ++i) unpack8(vraw[i], vf[i]);
+      for (int r = 0; r < kG; ++r) {
+        if (mask & (1u << r)) {
+          float mx = sp[r][0];
+#pragma unroll
+          for (int i = 1; i < kLoads; ++i) mx = fmaxf(mx, sp[r][i]);
+          const float m_new = fmaxf(m_run[r], mx);
+          const float alpha = __builtin_amdgcn_exp2f(m_run[r] - m_new);
+          float psum = 0.f;
+#pragma unroll
+          for (int i = 0; i < kLoads; ++i) {
+            const bool valid = t0 + i * kTPL < geo.n_tokens;
+            sp[r][i] = valid ? __builtin_amdgcn_exp2f(sp[r][i] - m_new) : 0.f;
+            psum += sp[r][i];
+          }
+          l_run[r] = l_run[r] * alpha + psum;
+          m_run[r] = m_new;
+          if (__ballot(alpha != 1.f)) {  // the maximum moved somewhere in the wave (rare once warmed up)
+#pragma unroll
+            for (int c = 0; c < 8; ++c) acc[r][c] *= alpha;
+          }
+        }
+      }
+      // acc += p * v
+#pragma unroll
+      for (int i = 0; i < kLoads; ++i) {
+        float vf[8];
+        unpack8(vraw[i], vf);
 #pragma unroll
         for (int r = 0; r < kG; ++r) {
           if (mask & (1u << r)) {
 #pragma unroll
-            for (int c = 0; c < 8; ++c) {
-              float a = acc[r][c] * alpha[r];
-#pragma unroll
-              for (int i = 0; i < kLoads; ++i) a = fmaf(p[r][i], vf[i][c], a);
-              acc[r][c] = a;
-            }
+            for (int c = 0; c < 8; ++c) acc[r][c] = fmaf(sp[r][i], vf[c], acc[r][c]);
           }
         }
       }
@@ -269,24 +289,57 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
   }
 }
 
+// One workgroup per (sequence, query head).  Pass 1 finds the global maximum over the group's items;
+// pass 2 spreads the items over 256 / (kD/4) slices of threads, each thread owning 4 channels, and adds
+// acc * 2^(m - M) (items whose sum is zero -- the head was not in the item's masks -- are skipped);
+// the slices are then summed in a fixed order.
 template <int kD>
-__global__ __launch_bounds__(kD) void merge_kernel(Params P, const int32_t* __restrict__ sched,
-                                                   const float* __restrict__ acc_part,
-                                                   const float* __restrict__ ml_part, float* __restrict__ out,
-                                                   int items_cap) {
-  const int b = blockIdx.y, h = blockIdx.x, c = threadIdx.x;
+__global__ __launch_bounds__(256) void merge_kernel(Params P, const int32_t* __restrict__ sched,
+                                                    const float* __restrict__ acc_part,
+                                                    const float* __restrict__ ml_part, float* __restrict__ out,
+                                                    int items_cap) {
+  constexpr int kLanesC = kD / 4;          // threads per item (4 channels each)
+  constexpr int kSlices = 256 / kLanesC;   // items in flight per pass-2 iteration
+  __shared__ float s_max[4];
+  __shared__ float s_o[kSlices][kD];
+  __shared__ float s_l[kSlices];
+  const int b = blockIdx.y, h = blockIdx.x, tid = threadIdx.x;
   const int G = P.group, j = h / G, r = h % G;
   const int grp = b * P.n_kv_heads + j;
   const int p0 = min(sched[grp], items_cap), p1 = min(sched[grp + 1], items_cap);
+
   float M = kNegBig;
-  for (int it = p0; it < p1; ++it) M = fmaxf(M, ml_part[((int64_t)it * G + r) * 2]);
-  float o = 0.f, L = 0.f;
-  for (int it = p0; it < p1; ++it) {
-    const float w = __builtin_amdgcn_exp2f(ml_part[((int64_t)it * G + r) * 2] - M);
-    L += ml_part[((int64_t)it * G + r) * 2 + 1] * w;
-    o += acc_part[((int64_t)it * G + r) * kD + c] * w;
+  for (int it = p0 + tid; it < p1; it += 256) M = fmaxf(M, ml_part[((int64_t)it * G + r) * 2]);
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) M = fmaxf(M, __shfl_xor(M, off, kWave));
+  if ((tid & 63) == 0) s_max[tid >> 6] = M;
+  __syncthreads();
+  M = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
+
+  const int slice = tid / kLanesC, cl = tid % kLanesC;
+  float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+  float L = 0.f;
+  for (int it = p0 + slice; it < p1; it += kSlices) {
+    const float2 ml = *reinterpret_cast<const float2*>(ml_part + ((int64_t)it * G + r) * 2);
+    if (ml.y > 0.f) {
+      const float w = __builtin_amdgcn_exp2f(ml.x - M);
+      const float4 a = *reinterpret_cast<const float4*>(acc_part + ((int64_t)it * G + r) * kD + cl * 4);
+      L += ml.y * w;
+      o.x += a.x * w; o.y += a.y * w; o.z += a.z * w; o.w += a.w * w;
+    }
   }
-  out[((int64_t)b * P.n_q_heads + h) * kD + c] = L > 0.f ? o / L : 0.f;
+  *reinterpret_cast<float4*>(&s_o[slice][cl * 4]) = o;
+  if (cl == 0) s_l[slice] = L;
+  __syncthreads();
+  if (tid < kD) {
+    float acc = 0.f, Lt = 0.f;
+#pragma unroll
+    for (int sl = 0; sl < kSlices; ++sl) {
+      acc += s_o[sl][tid];
+      Lt += s_l[sl];
+    }
+    out[((int64_t)b * P.n_q_heads + h) * kD + tid] = Lt > 0.f ? acc / Lt : 0.f;
+  }
 }
 
 template <int kD, int kG>
@@ -349,10 +402,10 @@ hipError_t launch_decode(const Params& P, const void* q, const void* K, const vo
   if (e != hipSuccess) return e;
   ScopedSlot prof(kSlotMerge, stream);
   if (P.head_dim == 128)
-    hipLaunchKernelGGL(merge_kernel<128>, dim3(P.n_q_heads, P.batch), dim3(128), 0, stream, P, (const int32_t*)sched,
+    hipLaunchKernelGGL(merge_kernel<128>, dim3(P.n_q_heads, P.batch), dim3(256), 0, stream, P, (const int32_t*)sched,
                        (const float*)acc_part, (const float*)ml_part, out, W.items_cap);
   else
-    hipLaunchKernelGGL(merge_kernel<64>, dim3(P.n_q_heads, P.batch), dim3(64), 0, stream, P, (const int32_t*)sched,
+    hipLaunchKernelGGL(merge_kernel<64>, dim3(P.n_q_heads, P.batch), dim3(256), 0, stream, P, (const int32_t*)sched,
                        (const float*)acc_part, (const float*)ml_part, out, W.items_cap);
   return hipGetLastError();
 }

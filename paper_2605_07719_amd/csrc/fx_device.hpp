@@ -66,6 +66,12 @@ __device__ __forceinline__ uint4 pack8(const float* f) {
   return r;
 }
 
+// acc + a.lo * b.lo + a.hi * b.hi on two packed bf16 pairs (v_dot2c_f32_bf16): exact products, fp32 sum.
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), acc, false);
+}
+
 // Cross-lane moves inside a row of 16 lanes (DPP): every lane reads a partner, so "old" is unused.
 template <int kCtrl>
 __device__ __forceinline__ float dpp_f(float x) {

@@ -29,6 +29,7 @@ constexpr int kMinChunkTokens = 64;
 constexpr int kMaxChunkShift = 4;
 constexpr int kTargetItems = 4096;
 constexpr int kMaxGroups = 4096;
+constexpr int kMaxChunkEntries = (kMinChunkTokens << kMaxChunkShift) / 16;  // smallest block is 16 tokens
 
 // fx_sparse_decode scratch.
 struct DecodeWorkspace {

@@ -1,0 +1,71 @@
+// Measurement aids (not part of the method): a plain streaming read and a plain copy of a device
+// buffer.  The benchmark uses them to state the HBM read rate this machine reaches with no arithmetic at
+// all, and to scale hardware-counter readings against a transfer of known size.
+#include "../../include/fluxion.h"
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace {
+
+constexpr int kUnroll = 8;
+
+__global__ __launch_bounds__(256) void probe_read_kernel(const uint4* __restrict__ src, size_t n16,
+                                                         uint32_t* __restrict__ sink) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  uint4 acc = make_uint4(0, 0, 0, 0);
+  for (; i + (kUnroll - 1) * stride < n16; i += kUnroll * stride) {
+    uint4 v[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) v[u] = src[i + u * stride];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      acc.x ^= v[u].x; acc.y ^= v[u].y; acc.z ^= v[u].z; acc.w ^= v[u].w;
+    }
+  }
+  for (; i < n16; i += stride) {
+    uint4 v = src[i];
+    acc.x ^= v.x; acc.y ^= v.y; acc.z ^= v.z; acc.w ^= v.w;
+  }
+  // data-dependent, practically never true: keeps the loads alive without a store per thread
+  if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) sink[0] = acc.x;
+}
+
+__global__ __launch_bounds__(256) void probe_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
+                                                         size_t n16) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+int grid_for(int wg_per_cu) {
+  int dev = 0, n = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+    n = 256;
+  if (wg_per_cu < 1) wg_per_cu = 1;
+  if (wg_per_cu > 32) wg_per_cu = 32;
+  return n * wg_per_cu;
+}
+
+}  // namespace
+
+extern "C" {
+
+fx_status fx_probe_read(const void* src, size_t bytes, void* sink, int wg_per_cu, void* stream) {
+  if (!src || !sink || bytes < 16 || (reinterpret_cast<uintptr_t>(src) & 15u)) return FX_ERR_INVALID_ARG;
+  hipLaunchKernelGGL(probe_read_kernel, dim3(grid_for(wg_per_cu)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const uint4*>(src), bytes / 16, static_cast<uint32_t*>(sink));
+  return hipGetLastError() == hipSuccess ? FX_OK : FX_ERR_HIP;
+}
+
+fx_status fx_probe_copy(void* dst, const void* src, size_t bytes, int wg_per_cu, void* stream) {
+  if (!src || !dst || bytes < 16 || (reinterpret_cast<uintptr_t>(src) & 15u) ||
+      (reinterpret_cast<uintptr_t>(dst) & 15u))
+    return FX_ERR_INVALID_ARG;
+  hipLaunchKernelGGL(probe_copy_kernel, dim3(grid_for(wg_per_cu)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const uint4*>(src), static_cast<uint4*>(dst), bytes / 16);
+  return hipGetLastError() == hipSuccess ? FX_OK : FX_ERR_HIP;
+}
+
+}  // extern "C"

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libfluxion.so")
 
 EXPORTS = (
     "fx_status_string", "fx_summarize", "fx_select_workspace_bytes", "fx_select", "fx_decode_workspace_bytes",
-    "fx_sparse_decode", "fx_profile_enable", "fx_profile_read",
+    "fx_sparse_decode", "fx_profile_enable", "fx_profile_read", "fx_probe_read", "fx_probe_copy",
 )
 
 FX_OK, FX_ERR_INVALID_ARG, FX_ERR_UNSUPPORTED, FX_ERR_WORKSPACE_TOO_SMALL, FX_ERR_HIP = range(5)
@@ -75,6 +75,10 @@ def lib() -> ctypes.CDLL:
         L.fx_profile_enable.argtypes = [ctypes.c_int]
         L.fx_profile_read.restype = ctypes.c_int
         L.fx_profile_read.argtypes = [ctypes.c_void_p, ctypes.c_int]
+        L.fx_probe_read.restype = ctypes.c_int
+        L.fx_probe_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
+        L.fx_probe_copy.restype = ctypes.c_int
+        L.fx_probe_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p]
         _lib = L
     return _lib
 
@@ -204,3 +208,16 @@ def profile_read() -> dict:
     ms = (ctypes.c_float * len(PROFILE_SLOTS))()
     _check(lib().fx_profile_read(ms, len(PROFILE_SLOTS)), "fx_profile_read")
     return {name: float(ms[i]) for i, name in enumerate(PROFILE_SLOTS)}
+
+
+def probe_read(src: torch.Tensor, sink: torch.Tensor, wg_per_cu: int = 8, stream=None) -> None:
+    """fx_probe_read: plain streaming read of the whole tensor (measurement aid)."""
+    _check(lib().fx_probe_read(_dptr(src), src.numel() * src.element_size(), _dptr(sink), wg_per_cu, _stream(stream)),
+           "fx_probe_read")
+
+
+def probe_copy(dst: torch.Tensor, src: torch.Tensor, wg_per_cu: int = 8, stream=None) -> None:
+    """fx_probe_copy: plain copy src -> dst (measurement aid)."""
+    n = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() >= n
+    _check(lib().fx_probe_copy(_dptr(dst), _dptr(src), n, wg_per_cu, _stream(stream)), "fx_probe_copy")
