@@ -147,6 +147,20 @@ fx_status fx_select(const fx_layout* layout, const void* q, const void* summarie
              : FX_ERR_HIP;
 }
 
+fx_status fx_select_workspace_view(const fx_layout* layout, size_t* approx_offset, size_t* mag_offset,
+                                   int64_t* row_stride, float* gamma) {
+  fx::Params P;
+  fx_status st = make_params(layout, 0, 0, 1, &P);
+  if (st != FX_OK) return st;
+  if (!approx_offset || !mag_offset || !row_stride || !gamma) return FX_ERR_INVALID_ARG;
+  const fx::SelectWorkspace W = fx::carve_select(P);
+  *approx_offset = W.approx_off;
+  *mag_offset = W.mag_off;
+  *row_stride = P.nb_stride;
+  *gamma = fx::select_error_gamma();
+  return FX_OK;
+}
+
 size_t fx_decode_workspace_bytes(const fx_layout* layout, int32_t k_max, int32_t sink_tokens, int32_t window_tokens) {
   fx::Params P;
   if (make_params(layout, sink_tokens, window_tokens, k_max, &P) != FX_OK) return 0;

@@ -12,14 +12,19 @@ namespace fx {
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
-// fx_select scratch: one order-preserving 64-bit key per (sequence, query head, block).
+// fx_select scratch, per (sequence, query head, block): the approximate score and its magnitude sum
+// (fp32 each) and, for the exact fallback path, one order-preserving 64-bit key.
 struct SelectWorkspace {
-  size_t keys_off, total;
+  size_t approx_off, mag_off, keys_off, total;
 };
 inline SelectWorkspace carve_select(const Params& P) {
   SelectWorkspace W;
-  W.keys_off = 0;
-  W.total = align_up((size_t)P.batch * P.n_q_heads * P.nb_stride * sizeof(uint64_t));
+  const size_t n = (size_t)P.batch * P.n_q_heads * P.nb_stride;
+  size_t off = 0;
+  W.approx_off = off; off += align_up(n * sizeof(float));
+  W.mag_off = off;    off += align_up(n * sizeof(float));
+  W.keys_off = off;   off += align_up(n * sizeof(uint64_t));
+  W.total = off;
   return W;
 }
 
@@ -93,6 +98,7 @@ struct ScopedSlot {  // records start on construction and stop on destruction, o
   }
 };
 
+float select_error_gamma();
 hipError_t launch_summarize(const Params& P, const void* K, void* S, hipStream_t stream);
 hipError_t launch_select(const Params& P, const void* q, const void* S, const float* budget_frac,
                          const int32_t* budget_blocks, int32_t* idx, int32_t* cnt, void* workspace,

@@ -2,139 +2,171 @@
 // of all key blocks and the top-k blocks are selected; Sec. 5.3: one block size per GQA group, one
 // budget per head).
 //
-// Stage 1 (score_kernel) streams the candidate summaries of one (sequence, KV head) once and scores
-// them for up to 4 query heads of the group at a time:
-//     score = sum_c max(q_c * mn_c, q_c * mx_c) = sum_c (max(q_c,0) * mx_c + min(q_c,0) * mn_c),
-// every product is exact and the sum is accumulated in fp64, so the ranking agrees with an fp64
-// evaluation except for candidates that are equal to ~1e-15.  Scores leave the kernel as 64-bit
-// keys whose unsigned order is the order of the scores.
-// Stage 2 (topk_kernel) finds, per (sequence, query head), the k-th largest key by a most-significant
-// -digit-first radix select (8 passes of 8 bits), then writes the kept block indices in ascending
-// order; among keys equal to the k-th the lowest block indices are kept.
+// The score of a block for a head is  s = sum_c max(q_c mn_c, q_c mx_c)
+//                                       = sum_c (min(q_c,0) mn_c + max(q_c,0) mx_c),
+// i.e. one row of a dense product  [q- | q+] (G x 2d)  times  [mn | mx]^T (2d x n_cand): the summary
+// rows are stored exactly as [mn | mx], so the stream of summaries feeds the matrix cores directly.
+//
+// Stage 1 (score_kernel): per (sequence, KV head) stream the candidate summaries once; bf16 MFMA
+//   (16x16x32, fp32 accumulate) gives, for all heads of the group at once, an approximate score
+//   s~ and the magnitude sum a~ = sum_c (|q-_c| |mn_c| + |q+_c| |mx_c|) that bounds its rounding error.
+// Stage 2 (topk_kernel): per (sequence, query head) a radix select on the fp32 keys finds the k-th
+//   largest s~ = T.  With eps = gamma * max a~, every candidate above T + 2 eps is certainly among
+//   the exact top-k and every candidate below T - 2 eps certainly is not.  Only the few candidates
+//   inside the band are re-scored exactly (exact products, fp64 accumulation) and ranked by
+//   (exact score descending, index ascending).  The result therefore equals the selection made on
+//   fp64 scores (up to fp64 summation order, ~1e-16), while the bulk of the work runs at the speed
+//   the summaries stream from HBM.  If the band holds more candidates than fit in LDS (masses of
+//   identical blocks) the head falls back to exact scores for all candidates and a 64-bit radix select.
 #include "fx_device.hpp"
 #include "fx_kernels.hpp"
 
 namespace fx {
 
-__device__ __forceinline__ uint64_t ordered_key(double s) {
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+// Bound on |s~ - s| / a~.  Products of bf16 pairs are exact in fp32; a chain of 2d <= 256 fp32
+// accumulations is off by at most 256 * 2^-24 a~ = 2^-16 a~ with round-to-nearest adds and 2^-15 a~
+// with truncating adds.  2^-14 leaves a factor of two over the worse case; the GPU tests check the
+// measured error of every candidate against this bound.
+constexpr float kGamma = 1.0f / 16384.0f;
+constexpr int kAmbCap = 256;  // band candidates re-scored in LDS; more => fallback
+
+__device__ __forceinline__ uint64_t ordered_key64(double s) {
   uint64_t u = (uint64_t)__double_as_longlong(s);
   return (u >> 63) ? ~u : (u | 0x8000000000000000ull);
 }
+__device__ __forceinline__ uint32_t ordered_key32(float s) {
+  uint32_t u = __float_as_uint(s);
+  return (u >> 31) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float key32_to_float(uint32_t k) {
+  return __uint_as_float((k >> 31) ? (k & 0x7fffffffu) : ~k);
+}
 
-template <int kD, int kHP>
+// ---------------------------------------------------------------------------------------------------
+// Stage 1
+// ---------------------------------------------------------------------------------------------------
+// MFMA operand layout (v_mfma_f32_16x16x32_bf16): lane l supplies A[m = l % 16][k = 8 (l / 16) .. + 8]
+// and B[k = 8 (l / 16) .. + 8][n = l % 16]; it receives D[m = 4 (l / 16) + i][n = l % 16], i = 0..3.
+// Here n = candidate within a tile of 16, k = position in the [mn | mx] row, and the A rows are
+//   m = 0..7 : [q- | q+] of head m of the group      (-> s~, from B)
+//   m = 8..15: [|q-| | |q+|] of head m - 8            (-> a~, from |B|)
+template <int kD>
 __global__ __launch_bounds__(256) void score_kernel(Params P, const uint16_t* __restrict__ q,
-                                                    const uint16_t* __restrict__ S, uint64_t* __restrict__ keys) {
-  constexpr int kLanes = kD / 8;
-  constexpr int kCandPerIter = 256 / kLanes;
-  constexpr int kIters = 4;
-  constexpr int kTile = kCandPerIter * kIters;
-  const int n_pass = (P.group + kHP - 1) / kHP;
-  const int b = blockIdx.z, j = blockIdx.y / n_pass, pass = blockIdx.y % n_pass;
+                                                    const uint16_t* __restrict__ S, float* __restrict__ approx,
+                                                    float* __restrict__ mag) {
+  constexpr int kRow = 2 * kD;       // elements of one [mn | mx] row
+  constexpr int kSlabs = kRow / 32;  // MFMA k-steps per row
+  constexpr int kTilesPerWave = 2;
+  const int b = blockIdx.z, j = blockIdx.y;
   const Geo geo = geometry(P, b, j);
-  const int tile0 = blockIdx.x * kTile;
-  if (tile0 >= geo.n_cand) return;
-  const int chunk = threadIdx.x % kLanes;
-  const int slot = threadIdx.x / kLanes;
-  const int h0 = j * P.group + pass * kHP;
-  const int nh = min(kHP, P.group - pass * kHP);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n = lane & 15, r = lane >> 4;
+  const int tile_first = (blockIdx.x * 4 + wave) * kTilesPerWave;
+  if (tile_first * 16 >= geo.n_cand) return;
 
-  double qp[kHP][8], qn[kHP][8];
+  // A operand, built once per wave from q
+  uint4 a_op[kSlabs];
+  {
+    const int head = n & 7;
+    const bool want_abs = n >= 8;
 #pragma unroll
-  for (int r = 0; r < kHP; ++r) {
-    float x[8];
-    if (r < nh) {
-      uint4 raw = *reinterpret_cast<const uint4*>(q + ((int64_t)b * P.n_q_heads + h0 + r) * kD + chunk * 8);
-      unpack8(raw, x);
-    } else {
+    for (int s = 0; s < kSlabs; ++s) {
+      const int e = 32 * s + 8 * r;  // first row element of this lane's k-chunk
+      const int c = e % kD;
+      const bool is_mx = e >= kD;
+      float x[8];
+      if (head < P.group) {
+        const uint4 raw =
+            *reinterpret_cast<const uint4*>(q + ((int64_t)b * P.n_q_heads + j * P.group + head) * kD + c);
+        unpack8(raw, x);
+      } else {
 #pragma unroll
-      for (int c = 0; c < 8; ++c) x[c] = 0.f;
-    }
+        for (int t = 0; t < 8; ++t) x[t] = 0.f;
+      }
 #pragma unroll
-    for (int c = 0; c < 8; ++c) {
-      qp[r][c] = (double)fmaxf(x[c], 0.f);
-      qn[r][c] = (double)fminf(x[c], 0.f);
+      for (int t = 0; t < 8; ++t) {
+        const float part = is_mx ? fmaxf(x[t], 0.f) : fminf(x[t], 0.f);
+        x[t] = want_abs ? fabsf(part) : part;
+      }
+      a_op[s] = pack8(x);
     }
   }
 
-  const uint16_t* sum_row =
-      S + (P.sum_base[(int64_t)b * P.n_kv_heads + j] + geo.n_sink) * 2 * (int64_t)kD + chunk * 8;
-  uint4 raw_mn[kIters], raw_mx[kIters];
+  const uint16_t* rows = S + (P.sum_base[(int64_t)b * P.n_kv_heads + j] + geo.n_sink) * (int64_t)kRow + r * 8;
+  uint4 b_op[kTilesPerWave][kSlabs];
 #pragma unroll
-  for (int it = 0; it < kIters; ++it) {
-    const int r = tile0 + it * kCandPerIter + slot;
-    const int rc = min(r, geo.n_cand - 1);  // clamped: stays inside the candidate range
-    const uint16_t* p = sum_row + (int64_t)rc * 2 * kD;
-    raw_mn[it] = *reinterpret_cast<const uint4*>(p);
-    raw_mx[it] = *reinterpret_cast<const uint4*>(p + kD);
+  for (int t = 0; t < kTilesPerWave; ++t) {
+    const int cand = min((tile_first + t) * 16 + n, geo.n_cand - 1);  // clamped: stays inside the candidates
+    const uint16_t* p = rows + (int64_t)cand * kRow;
+#pragma unroll
+    for (int s = 0; s < kSlabs; ++s) b_op[t][s] = *reinterpret_cast<const uint4*>(p + 32 * s);
   }
 #pragma unroll
-  for (int it = 0; it < kIters; ++it) {
-    const int r = tile0 + it * kCandPerIter + slot;
-    float fmn[8], fmx[8];
-    unpack8(raw_mn[it], fmn);
-    unpack8(raw_mx[it], fmx);
-    double dmn[8], dmx[8];
+  for (int t = 0; t < kTilesPerWave; ++t) {
+    f32x4_t d_s = {0.f, 0.f, 0.f, 0.f}, d_a = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int c = 0; c < 8; ++c) {
-      dmn[c] = (double)fmn[c];
-      dmx[c] = (double)fmx[c];
+    for (int s = 0; s < kSlabs; ++s) {
+      const uint4 v = b_op[t][s];
+      const uint4 va = make_uint4(v.x & 0x7fff7fffu, v.y & 0x7fff7fffu, v.z & 0x7fff7fffu, v.w & 0x7fff7fffu);
+      d_s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a_op[s]),
+                                                    __builtin_bit_cast(bf16x8_t, v), d_s, 0, 0, 0);
+      d_a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a_op[s]),
+                                                    __builtin_bit_cast(bf16x8_t, va), d_a, 0, 0, 0);
     }
+    const int cand = (tile_first + t) * 16 + n;
+    if (cand < geo.n_cand) {
+      float* dst = r < 2 ? approx : mag;
 #pragma unroll
-    for (int hh = 0; hh < kHP; ++hh) {
-      if (hh < nh) {
-        double acc = 0.0;
-#pragma unroll
-        for (int c = 0; c < 8; ++c) acc = fma(qp[hh][c], dmx[c], fma(qn[hh][c], dmn[c], acc));
-#pragma unroll
-        for (int off = 1; off < kLanes; off <<= 1) acc += __shfl_xor(acc, off, kWave);
-        if (chunk == 0 && r < geo.n_cand)
-          keys[((int64_t)b * P.n_q_heads + h0 + hh) * P.nb_stride + geo.n_sink + r] = ordered_key(acc);
+      for (int i = 0; i < 4; ++i) {
+        const int head = (4 * r + i) & 7;
+        if (head < P.group)
+          dst[((int64_t)b * P.n_q_heads + j * P.group + head) * P.nb_stride + geo.n_sink + cand] =
+              r < 2 ? d_s[i] : d_a[i];
       }
     }
   }
 }
 
-__global__ __launch_bounds__(256) void topk_kernel(Params P, const uint64_t* __restrict__ keys,
-                                                   const float* __restrict__ budget_frac,
-                                                   const int32_t* __restrict__ budget_blocks,
-                                                   int32_t* __restrict__ idx, int32_t* __restrict__ cnt) {
-  __shared__ int hist[256];
-  __shared__ int scan_scratch[4];
-  __shared__ int count_scratch_a[4];
-  __shared__ int count_scratch_b[4];
-  __shared__ int s_digit, s_krem;
+// ---------------------------------------------------------------------------------------------------
+// Stage 2
+// ---------------------------------------------------------------------------------------------------
 
-  const int b = blockIdx.y, h = blockIdx.x, j = h / P.group;
+// Exact score of one candidate for one head, computed by a whole wave: exact products, fp64 sums.
+// Every lane returns the same value.
+template <int kD>
+__device__ __forceinline__ double exact_score_wave(const uint16_t* __restrict__ q_h, const uint16_t* __restrict__ row,
+                                                   int lane) {
+  constexpr int kPer = kD / 64;  // channels per lane (1 or 2)
+  double acc = 0.0;
+#pragma unroll
+  for (int t = 0; t < kPer; ++t) {
+    const int c = lane * kPer + t;
+    const double qc = (double)__uint_as_float((uint32_t)q_h[c] << 16);
+    const double mn = (double)__uint_as_float((uint32_t)row[c] << 16);
+    const double mx = (double)__uint_as_float((uint32_t)row[kD + c] << 16);
+    acc = fma(fmax(qc, 0.0), mx, fma(fmin(qc, 0.0), mn, acc));
+  }
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) acc += __shfl_xor(acc, off, kWave);
+  return acc;
+}
+
+// Most-significant-digit-first radix select over `n` keys read through `load(r)`: returns the k-th
+// largest key and how many of the keys equal to it belong to the top k.  256 threads; `hist` is
+// 256 ints of LDS, `scan_scratch` 4 ints, `s_pair` 2 ints.
+template <typename KeyT, typename Load>
+__device__ __forceinline__ void radix_select(Load load, int n, int k, int* hist, int* scan_scratch, int* s_pair,
+                                             KeyT& kth_out, int& krem_out) {
+  constexpr int kPasses = sizeof(KeyT);
   const int tid = threadIdx.x;
-  const Geo geo = geometry(P, b, j);
-  const int64_t slot = (int64_t)b * P.n_q_heads + h;
-  double want;
-  if (budget_blocks)
-    want = (double)budget_blocks[slot];
-  else
-    want = ceil((double)budget_frac[slot] * (double)geo.n_cand);
-  const int limit = geo.n_cand < P.k_max ? geo.n_cand : P.k_max;
-  const int k = want > 0.0 ? (want < (double)limit ? (int)want : limit) : 0;  // NaN falls to 0
-  int32_t* out = idx + slot * P.k_max;
-  const uint64_t* kh = keys + slot * P.nb_stride + geo.n_sink;
-  const int n = geo.n_cand;
-
-  if (tid == 0) cnt[slot] = k;
-  if (k == 0) {
-    for (int r = tid; r < P.k_max; r += 256) out[r] = -1;
-    return;
-  }
-  if (k == n) {
-    for (int r = tid; r < P.k_max; r += 256) out[r] = r < k ? geo.n_sink + r : -1;
-    return;
-  }
-
-  // Radix select of the k-th largest key: `prefix` holds the digits fixed so far.
-  uint64_t prefix = 0;
+  KeyT prefix = 0;
   int krem = k;
-  for (int pass = 7; pass >= 0; --pass) {
+  for (int pass = kPasses - 1; pass >= 0; --pass) {
     const int shift = pass * 8;
-    const uint64_t hi_mask = pass == 7 ? 0ull : (~0ull << (shift + 8));
+    const KeyT hi_mask = pass == kPasses - 1 ? (KeyT)0 : (KeyT)(~(KeyT)0 << (shift + 8));
     hist[tid] = 0;
     __syncthreads();
     for (int base = 0; base < n; base += 256) {
@@ -142,12 +174,12 @@ __global__ __launch_bounds__(256) void topk_kernel(Params P, const uint64_t* __r
       bool match = false;
       unsigned digit = 0;
       if (r < n) {
-        const uint64_t key = kh[r];
+        const KeyT key = load(r);
         match = (key & hi_mask) == prefix;
         digit = (unsigned)(key >> shift) & 255u;
       }
-      // One LDS atomic per wave when all matching lanes agree on the digit (the usual case for the
-      // sign/exponent digits), else one per lane.
+      // one LDS atomic per wave when all matching lanes agree on the digit (usual for the sign and
+      // exponent digits), else one per lane
       const unsigned long long mball = __ballot(match);
       if (mball) {
         const int leader = __ffsll((long long)mball) - 1;
@@ -161,62 +193,220 @@ __global__ __launch_bounds__(256) void topk_kernel(Params P, const uint64_t* __r
       }
     }
     __syncthreads();
-    const int dg = 255 - tid;  // thread t owns digit 255 - t, so a prefix sum over threads is a suffix sum over digits
+    const int dg = 255 - tid;  // thread t owns digit 255 - t: a prefix sum over threads is a suffix sum over digits
     const int c = hist[dg];
     const int incl = block_incl_scan(c, scan_scratch);
     const int excl = incl - c;
     if (excl < krem && krem <= incl) {
-      s_digit = dg;
-      s_krem = krem - excl;
+      s_pair[0] = dg;
+      s_pair[1] = krem - excl;
     }
     __syncthreads();
-    prefix |= (uint64_t)s_digit << shift;
-    krem = s_krem;
+    prefix |= (KeyT)s_pair[0] << shift;
+    krem = s_pair[1];
     __syncthreads();
   }
-  const uint64_t kth = prefix;  // the k-th largest key; `krem` of the keys equal to it are kept
+  kth_out = prefix;
+  krem_out = krem;
+}
 
-  int run_sel = 0, run_eq = 0;
+template <int kD>
+__global__ __launch_bounds__(256) void topk_kernel(Params P, const uint16_t* __restrict__ q,
+                                                   const uint16_t* __restrict__ S, const float* __restrict__ approx,
+                                                   const float* __restrict__ mag, uint64_t* __restrict__ keys64,
+                                                   const float* __restrict__ budget_frac,
+                                                   const int32_t* __restrict__ budget_blocks,
+                                                   int32_t* __restrict__ idx, int32_t* __restrict__ cnt) {
+  __shared__ int hist[256];
+  __shared__ int scan_scratch[4];
+  __shared__ int count_a[4];
+  __shared__ int count_b[4];
+  __shared__ int s_pair[2];
+  __shared__ float s_wmax[4];
+  __shared__ int amb_idx[kAmbCap];
+  __shared__ uint64_t amb_key[kAmbCap];
+  __shared__ unsigned char amb_chosen[kAmbCap];
+
+  const int b = blockIdx.y, h = blockIdx.x, j = h / P.group;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const Geo geo = geometry(P, b, j);
+  const int64_t slot = (int64_t)b * P.n_q_heads + h;
+  double want;
+  if (budget_blocks)
+    want = (double)budget_blocks[slot];
+  else
+    want = ceil((double)budget_frac[slot] * (double)geo.n_cand);
+  const int limit = geo.n_cand < P.k_max ? geo.n_cand : P.k_max;
+  const int k = want > 0.0 ? (want < (double)limit ? (int)want : limit) : 0;  // NaN falls to 0
+  int32_t* out = idx + slot * P.k_max;
+  const int n = geo.n_cand;
+  const float* ap = approx + slot * P.nb_stride + geo.n_sink;
+  const float* mg = mag + slot * P.nb_stride + geo.n_sink;
+
+  if (tid == 0) cnt[slot] = k;
+  if (k == 0) {
+    for (int r = tid; r < P.k_max; r += 256) out[r] = -1;
+    return;
+  }
+  if (k == n) {
+    for (int r = tid; r < P.k_max; r += 256) out[r] = r < k ? geo.n_sink + r : -1;
+    return;
+  }
+
+  // error bound of the approximate scores of this head
+  float amax = 0.f;
+  for (int r = tid; r < n; r += 256) amax = fmaxf(amax, mg[r]);
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) amax = fmaxf(amax, __shfl_xor(amax, off, kWave));
+  if (lane == 0) s_wmax[wave] = amax;
+  __syncthreads();
+  amax = fmaxf(fmaxf(s_wmax[0], s_wmax[1]), fmaxf(s_wmax[2], s_wmax[3]));
+  const float eps2 = 2.0f * kGamma * amax * 1.001f + 1e-30f;
+
+  uint32_t kth32;
+  int krem32;
+  radix_select<uint32_t>([&](int r) { return ordered_key32(ap[r]); }, n, k, hist, scan_scratch, s_pair, kth32, krem32);
+  const float T = key32_to_float(kth32);
+  const float hi = T + eps2, lo = T - eps2;
+
+  // classify: certainly kept (above the band) / ambiguous (inside the band)
+  int n_sure = 0, n_amb = 0;
+  {
+    int c_sure = 0, c_amb = 0;
+    for (int r = tid; r < n; r += 256) {
+      const float s = ap[r];
+      c_sure += s > hi;
+      c_amb += (s <= hi) && (s >= lo);
+    }
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      c_sure += __shfl_xor(c_sure, off, kWave);
+      c_amb += __shfl_xor(c_amb, off, kWave);
+    }
+    __syncthreads();
+    if (lane == 0) {
+      count_a[wave] = c_sure;
+      count_b[wave] = c_amb;
+    }
+    __syncthreads();
+    n_sure = count_a[0] + count_a[1] + count_a[2] + count_a[3];
+    n_amb = count_b[0] + count_b[1] + count_b[2] + count_b[3];
+  }
+  const int need = k - n_sure;  // 1 <= need <= n_amb by construction of the band around the k-th key
+  const uint16_t* q_h = q + slot * kD;
+  const uint16_t* rows = S + (P.sum_base[(int64_t)b * P.n_kv_heads + j] + geo.n_sink) * (int64_t)(2 * kD);
+
+  if (need < n_amb && n_amb > kAmbCap) {
+    // Fallback: exact fp64 scores for every candidate, then an exact 64-bit radix select.
+    uint64_t* kh = keys64 + slot * P.nb_stride + geo.n_sink;
+    for (int r = wave; r < n; r += 4) {
+      const double s = exact_score_wave<kD>(q_h, rows + (int64_t)r * 2 * kD, lane);
+      if (lane == 0) kh[r] = ordered_key64(s);
+    }
+    __threadfence_block();
+    __syncthreads();
+    uint64_t kth64;
+    int krem64;
+    radix_select<uint64_t>([&](int r) { return kh[r]; }, n, k, hist, scan_scratch, s_pair, kth64, krem64);
+    int run_sel = 0, run_eq = 0;
+    for (int base = 0; base < n; base += 256) {
+      const int r = base + tid;
+      const uint64_t key = r < n ? kh[r] : 0ull;
+      const bool gt = r < n && key > kth64;
+      const bool eq = r < n && key == kth64;
+      int tot_eq, tot_sel;
+      const int eq_before = run_eq + block_excl_count(eq, count_a, tot_eq);
+      const bool sel = gt || (eq && eq_before < krem64);
+      const int pos = run_sel + block_excl_count(sel, count_b, tot_sel);
+      if (sel && pos < P.k_max) out[pos] = geo.n_sink + r;
+      run_eq += tot_eq;
+      run_sel += tot_sel;
+    }
+    for (int r = k + tid; r < P.k_max; r += 256) out[r] = -1;
+    return;
+  }
+
+  const bool resolve = need < n_amb;  // otherwise every band candidate is kept and no exact score is needed
+  if (resolve) {
+    // band candidates, ascending by index, into LDS
+    int run = 0;
+    for (int base = 0; base < n; base += 256) {
+      const int r = base + tid;
+      const float s = r < n ? ap[r] : 0.f;
+      const bool amb = r < n && s <= hi && s >= lo;
+      int tot;
+      const int pos = run + block_excl_count(amb, count_a, tot);
+      if (amb) amb_idx[pos] = r;
+      run += tot;
+    }
+    __syncthreads();
+    for (int a = wave; a < n_amb; a += 4) {
+      const double s = exact_score_wave<kD>(q_h, rows + (int64_t)amb_idx[a] * 2 * kD, lane);
+      if (lane == 0) amb_key[a] = ordered_key64(s);
+    }
+    __syncthreads();
+    if (tid < n_amb) {
+      const uint64_t mine = amb_key[tid];
+      int rank = 0;
+      for (int a = 0; a < n_amb; ++a) {
+        const uint64_t other = amb_key[a];
+        rank += (other > mine) || (other == mine && a < tid);
+      }
+      amb_chosen[tid] = rank < need;
+    }
+    __syncthreads();
+  }
+
+  // ordered compaction of the kept candidates
+  int run_sel = 0, run_amb = 0;
   for (int base = 0; base < n; base += 256) {
     const int r = base + tid;
-    const uint64_t key = r < n ? kh[r] : 0ull;
-    const bool gt = r < n && key > kth;
-    const bool eq = r < n && key == kth;
-    int tot_eq, tot_sel;
-    const int eq_before = run_eq + block_excl_count(eq, count_scratch_a, tot_eq);
-    const bool sel = gt || (eq && eq_before < krem);
-    const int pos = run_sel + block_excl_count(sel, count_scratch_b, tot_sel);
+    const float s = r < n ? ap[r] : 0.f;
+    const bool sure = r < n && s > hi;
+    const bool amb = r < n && s <= hi && s >= lo;
+    int tot_amb, tot_sel;
+    const int a = run_amb + block_excl_count(amb, count_a, tot_amb);
+    const bool sel = sure || (amb && (!resolve || amb_chosen[a]));
+    const int pos = run_sel + block_excl_count(sel, count_b, tot_sel);
     if (sel && pos < P.k_max) out[pos] = geo.n_sink + r;
-    run_eq += tot_eq;
+    run_amb += tot_amb;
     run_sel += tot_sel;
   }
   for (int r = k + tid; r < P.k_max; r += 256) out[r] = -1;
 }
 
+float select_error_gamma() { return kGamma; }
+
 hipError_t launch_select(const Params& P, const void* q, const void* S, const float* budget_frac,
                          const int32_t* budget_blocks, int32_t* idx, int32_t* cnt, void* workspace,
                          hipStream_t stream) {
   const SelectWorkspace W = carve_select(P);
-  uint64_t* keys = reinterpret_cast<uint64_t*>(static_cast<char*>(workspace) + W.keys_off);
-  constexpr int kHP = 4;
-  const int n_pass = (P.group + kHP - 1) / kHP;
-  const int lanes = P.head_dim / 8;
-  const int tile = (256 / lanes) * 4;
-  dim3 sgrid((P.nb_stride + tile - 1) / tile, P.n_kv_heads * n_pass, P.batch);
+  char* ws = static_cast<char*>(workspace);
+  float* approx = reinterpret_cast<float*>(ws + W.approx_off);
+  float* mag = reinterpret_cast<float*>(ws + W.mag_off);
+  uint64_t* keys = reinterpret_cast<uint64_t*>(ws + W.keys_off);
   {
-  ScopedSlot prof(kSlotScore, stream);
-  if (P.head_dim == 128)
-    hipLaunchKernelGGL((score_kernel<128, kHP>), sgrid, dim3(256), 0, stream, P, (const uint16_t*)q,
-                       (const uint16_t*)S, keys);
-  else
-    hipLaunchKernelGGL((score_kernel<64, kHP>), sgrid, dim3(256), 0, stream, P, (const uint16_t*)q,
-                       (const uint16_t*)S, keys);
+    ScopedSlot prof(kSlotScore, stream);
+    const int cand_per_wg = 4 * 2 * 16;  // 4 waves x 2 tiles x 16 candidates
+    dim3 sgrid((P.nb_stride + cand_per_wg - 1) / cand_per_wg, P.n_kv_heads, P.batch);
+    if (P.head_dim == 128)
+      hipLaunchKernelGGL(score_kernel<128>, sgrid, dim3(256), 0, stream, P, (const uint16_t*)q, (const uint16_t*)S,
+                         approx, mag);
+    else
+      hipLaunchKernelGGL(score_kernel<64>, sgrid, dim3(256), 0, stream, P, (const uint16_t*)q, (const uint16_t*)S,
+                         approx, mag);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   ScopedSlot prof(kSlotTopk, stream);
-  hipLaunchKernelGGL(topk_kernel, dim3(P.n_q_heads, P.batch), dim3(256), 0, stream, P, (const uint64_t*)keys,
-                     budget_frac, budget_blocks, idx, cnt);
+  if (P.head_dim == 128)
+    hipLaunchKernelGGL(topk_kernel<128>, dim3(P.n_q_heads, P.batch), dim3(256), 0, stream, P, (const uint16_t*)q,
+                       (const uint16_t*)S, (const float*)approx, (const float*)mag, keys, budget_frac, budget_blocks,
+                       idx, cnt);
+  else
+    hipLaunchKernelGGL(topk_kernel<64>, dim3(P.n_q_heads, P.batch), dim3(256), 0, stream, P, (const uint16_t*)q,
+                       (const uint16_t*)S, (const float*)approx, (const float*)mag, keys, budget_frac, budget_blocks,
+                       idx, cnt);
   return hipGetLastError();
 }
 

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libfluxion.so")
 
 EXPORTS = (
     "fx_status_string", "fx_summarize", "fx_select_workspace_bytes", "fx_select", "fx_decode_workspace_bytes",
-    "fx_sparse_decode", "fx_profile_enable", "fx_profile_read", "fx_probe_read", "fx_probe_copy",
+    "fx_sparse_decode", "fx_profile_enable", "fx_profile_read", "fx_probe_read", "fx_probe_copy", "fx_select_workspace_view",
 )
 
 FX_OK, FX_ERR_INVALID_ARG, FX_ERR_UNSUPPORTED, FX_ERR_WORKSPACE_TOO_SMALL, FX_ERR_HIP = range(5)
@@ -152,6 +152,18 @@ class Layout:
 def select_workspace_bytes(layout: Layout) -> int:
     c = layout.c_struct()
     return int(lib().fx_select_workspace_bytes(ctypes.byref(c)))
+
+
+def select_workspace_view(layout: Layout) -> dict:
+    """fx_select_workspace_view: byte offsets of the approximate scores and their error magnitudes."""
+    c = layout.c_struct()
+    a, m = ctypes.c_size_t(), ctypes.c_size_t()
+    stride, gamma = ctypes.c_int64(), ctypes.c_float()
+    fn = lib().fx_select_workspace_view
+    fn.restype = ctypes.c_int
+    _check(fn(ctypes.byref(c), ctypes.byref(a), ctypes.byref(m), ctypes.byref(stride), ctypes.byref(gamma)),
+           "fx_select_workspace_view")
+    return {"approx_offset": a.value, "mag_offset": m.value, "row_stride": stride.value, "gamma": gamma.value}
 
 
 def decode_workspace_bytes(layout: Layout, k_max: int, sink_tokens: int, window_tokens: int) -> int:

@@ -215,3 +215,87 @@ def test_runs_are_reproducible():
         gp.select()
         b = gp.decode()
         assert torch.equal(a, b)
+
+
+def _select_intermediates(gp):
+    """Approximate scores and error magnitudes fx_select left in its workspace (test aid of the ABI)."""
+    v = gp.F.select_workspace_view(gp.layout)
+    wl = gp.wl
+    n = wl.batch * wl.n_q_heads * v["row_stride"]
+    raw = gp.ws_select.cpu().numpy()
+    approx = raw[v["approx_offset"] : v["approx_offset"] + 4 * n].view(np.float32)
+    mag = raw[v["mag_offset"] : v["mag_offset"] + 4 * n].view(np.float32)
+    shape = (wl.batch, wl.n_q_heads, v["row_stride"])
+    return approx.reshape(shape).astype(np.float64), mag.reshape(shape).astype(np.float64), v["gamma"]
+
+
+@pytest.mark.parametrize("name", ["d64_ragged_mixed_gran", "d128_g4", "d128_g7_ragged", "d128_g8_gran128"])
+def test_approximate_scores_stay_inside_the_error_bound(name):
+    """The exactness of the selection rests on |approx - exact| <= gamma * magnitude for every candidate;
+    check it against the oracle's fp64 scores, with a factor 8 to spare."""
+    wl = small_cases()[name]
+    t = W.make_layer(wl)
+    ref = run_oracle(wl, t)
+    gp = GpuProblem(wl, t, k_max=ref["k_max"])
+    gp.summarize()
+    gp.select()
+    torch.cuda.synchronize()
+    approx, mag, gamma = _select_intermediates(gp)
+    sc = ref["scores"]
+    ok = np.isfinite(sc)
+    nb = sc.shape[-1]
+    err = np.abs(approx[..., :nb][ok] - sc[ok])
+    bound = gamma * mag[..., :nb][ok]
+    print(f"  candidates {ok.sum()}, max err/magnitude {np.max(err / mag[..., :nb][ok]):.3e}, gamma {gamma:.3e}",
+          flush=True)
+    assert (mag[..., :nb][ok] >= np.abs(sc[ok]) * (1 - 1e-3)).all()
+    assert (err <= bound / 8).all()
+
+
+def test_mass_ties_take_the_exact_fallback_path():
+    """1300 identical (all-zero) blocks straddle the k-th place: far more near-threshold candidates than the
+    in-LDS re-scoring holds, so the head must fall back to exact scores for all candidates; ties still go to
+    the lowest indices."""
+    wl = W.Workload(name="ties2", n_q_heads=4, n_kv_heads=2, head_dim=128, seq_len=[32768], gran=[16, 32],
+                    sink_tokens=64, window_tokens=256, seed=13)
+    t = W.make_layer(wl)
+    t.K[:, 200 * 32 : 1500 * 16] = 0
+    L = oracle_layout(wl)
+    q, K, V = host_arrays(t)
+    S = O.summarize(L, K, threads=THREADS)
+    sc = O.scores(L, q, S, 64, 256, threads=THREADS)
+    gp = GpuProblem(wl, t, k_max=2048)
+    gp.summarize()
+    for k in (1000, 1700):
+        bud = np.full((1, 4), k, dtype=np.int32)
+        idx_o, cnt_o, gap, kth = O.select(L, q, S, budget_blocks=bud, sink_tokens=64, window_tokens=256, k_max=2048,
+                                          threads=THREADS)
+        idx, cnt = gp.select(budget_blocks=bud)
+        exempt, differ = compare_selection(idx.cpu().numpy(), cnt.cpu().numpy(), idx_o, cnt_o, gap, kth, sc, None)
+        assert differ == 0
+    assert (gap[0, :2] == 0.0).all()
+
+
+def test_biased_channels_with_heavy_cancellation():
+    """Keys with large same-sign offsets make block scores sums of large terms of both signs, so the
+    approximate scores are poor relative to the score gaps; the exact re-scoring inside the band must still
+    reproduce the oracle's selection."""
+    wl = W.Workload(name="bias", n_q_heads=8, n_kv_heads=2, head_dim=128, seq_len=[16384, 9000], gran=[16, 32],
+                    sink_tokens=64, window_tokens=256, budget_frac=np.full((2, 8), 0.1, dtype=np.float32), seed=17)
+    t = W.make_layer(wl)
+    offs = (torch.randn(2, 1, 128, generator=torch.Generator().manual_seed(1)) * 30).to(torch.bfloat16)
+    t.K += offs
+    ref = run_oracle(wl, t)
+    gp = GpuProblem(wl, t, k_max=ref["k_max"])
+    gp.summarize()
+    idx, cnt = gp.select()
+    exempt, differ = compare_selection(idx.cpu().numpy(), cnt.cpu().numpy(), ref["idx"], ref["cnt"], ref["gap"],
+                                       ref["kth"], ref["scores"], None)
+    approx, mag, gamma = _select_intermediates(gp)
+    ok = np.isfinite(ref["scores"])
+    nb = ref["scores"].shape[-1]
+    err = np.abs(approx[..., :nb][ok] - ref["scores"][ok])
+    print(f"  near-tie heads {exempt}, differing {differ}, max err/magnitude {np.max(err / mag[..., :nb][ok]):.3e}",
+          flush=True)
+    assert (err <= gamma * mag[..., :nb][ok] / 8).all()
+    assert differ == 0
