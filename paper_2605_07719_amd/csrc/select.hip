@@ -375,6 +375,223 @@ __global__ __launch_bounds__(256) void topk_kernel(Params P, const uint16_t* __r
   for (int r = k + tid; r < P.k_max; r += 256) out[r] = -1;
 }
 
+// Register-resident variant for n_cand <= 256 * KPT: thread t owns the KPT consecutive candidates
+// t * KPT .. so that index order is thread order and every ordered compaction costs one block scan.
+// Keys are reduced to (key - smallest key) before the radix passes, which removes the sign/exponent
+// digits all candidates share: the select takes ceil(log2(span) / 8) passes, usually 3.
+template <int kD, int KPT>
+__global__ __launch_bounds__(256) void topk_reg_kernel(Params P, const uint16_t* __restrict__ q,
+                                                       const uint16_t* __restrict__ S,
+                                                       const float* __restrict__ approx,
+                                                       const float* __restrict__ mag, uint64_t* __restrict__ keys64,
+                                                       const float* __restrict__ budget_frac,
+                                                       const int32_t* __restrict__ budget_blocks,
+                                                       int32_t* __restrict__ idx, int32_t* __restrict__ cnt) {
+  __shared__ int hist[256];
+  __shared__ int scan_scratch[4];
+  __shared__ int count_a[4];
+  __shared__ int count_b[4];
+  __shared__ int s_pair[2];
+  __shared__ int s_tot;
+  __shared__ float s_wmax[4];
+  __shared__ uint32_t s_kmin[4], s_kmax[4];
+  __shared__ int amb_idx[kAmbCap];
+  __shared__ uint64_t amb_key[kAmbCap];
+  __shared__ unsigned char amb_chosen[kAmbCap];
+
+  const int b = blockIdx.y, h = blockIdx.x, j = h / P.group;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const Geo geo = geometry(P, b, j);
+  const int64_t slot = (int64_t)b * P.n_q_heads + h;
+  double want;
+  if (budget_blocks)
+    want = (double)budget_blocks[slot];
+  else
+    want = ceil((double)budget_frac[slot] * (double)geo.n_cand);
+  const int limit = geo.n_cand < P.k_max ? geo.n_cand : P.k_max;
+  const int k = want > 0.0 ? (want < (double)limit ? (int)want : limit) : 0;  // NaN falls to 0
+  int32_t* out = idx + slot * P.k_max;
+  const int n = geo.n_cand;
+  const float* ap = approx + slot * P.nb_stride + geo.n_sink;
+  const float* mg = mag + slot * P.nb_stride + geo.n_sink;
+
+  if (tid == 0) cnt[slot] = k;
+  if (k == 0) {
+    for (int r = tid; r < P.k_max; r += 256) out[r] = -1;
+    return;
+  }
+  if (k == n) {
+    for (int r = tid; r < P.k_max; r += 256) out[r] = r < k ? geo.n_sink + r : -1;
+    return;
+  }
+
+  // keys of this thread's candidates (0 = no candidate: below every real key), error bound, key range
+  const int r0 = tid * KPT;
+  uint32_t key[KPT];
+  float amax = 0.f;
+  uint32_t kmin = 0xffffffffu, kmax = 0u;
+#pragma unroll
+  for (int i = 0; i < KPT; ++i) {
+    const int r = r0 + i;
+    key[i] = 0u;
+    if (r < n) {
+      key[i] = ordered_key32(ap[r]);
+      amax = fmaxf(amax, mg[r]);
+      kmin = min(kmin, key[i]);
+      kmax = max(kmax, key[i]);
+    }
+  }
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    amax = fmaxf(amax, __shfl_xor(amax, off, kWave));
+    kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, off, kWave));
+    kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, off, kWave));
+  }
+  if (lane == 0) {
+    s_wmax[wave] = amax;
+    s_kmin[wave] = kmin;
+    s_kmax[wave] = kmax;
+  }
+  __syncthreads();
+  amax = fmaxf(fmaxf(s_wmax[0], s_wmax[1]), fmaxf(s_wmax[2], s_wmax[3]));
+  kmin = min(min(s_kmin[0], s_kmin[1]), min(s_kmin[2], s_kmin[3]));
+  kmax = max(max(s_kmax[0], s_kmax[1]), max(s_kmax[2], s_kmax[3]));
+  const float eps2 = 2.0f * kGamma * amax * 1.001f + 1e-30f;
+
+  // radix select of the k-th largest key on u = key - kmin, most significant digit first
+  const uint32_t span = kmax - kmin;
+  const int n_bits = span ? 32 - __clz((int)span) : 0;
+  uint32_t prefix = 0;
+  int krem = k;
+  for (int pass = (n_bits + 7) / 8 - 1; pass >= 0; --pass) {
+    const int shift = pass * 8;
+    const uint32_t hi_mask = shift + 8 >= 32 ? 0u : (~0u << (shift + 8));
+    hist[tid] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < KPT; ++i) {
+      const uint32_t u = key[i] - kmin;
+      if (key[i] != 0u && (u & hi_mask) == prefix) atomicAdd(&hist[(u >> shift) & 255u], 1);
+    }
+    __syncthreads();
+    const int dg = 255 - tid;
+    const int c = hist[dg];
+    const int incl = block_incl_scan(c, scan_scratch);
+    const int excl = incl - c;
+    if (excl < krem && krem <= incl) {
+      s_pair[0] = dg;
+      s_pair[1] = krem - excl;
+    }
+    __syncthreads();
+    prefix |= (uint32_t)s_pair[0] << shift;
+    krem = s_pair[1];
+    __syncthreads();
+  }
+  const float T = key32_to_float(kmin + prefix);
+  const uint32_t hi_key = ordered_key32(T + eps2), lo_key = ordered_key32(T - eps2);
+
+  // classify this thread's candidates: certainly kept / inside the band
+  int c_sure = 0, c_amb = 0;
+#pragma unroll
+  for (int i = 0; i < KPT; ++i) {
+    c_sure += key[i] > hi_key;
+    c_amb += key[i] >= lo_key && key[i] <= hi_key;
+  }
+  const int sure_incl = block_incl_scan(c_sure, scan_scratch);
+  if (tid == 255) s_tot = sure_incl;
+  __syncthreads();
+  const int n_sure = s_tot;
+  const int amb_incl = block_incl_scan(c_amb, scan_scratch);
+  if (tid == 255) s_tot = amb_incl;
+  __syncthreads();
+  const int n_amb = s_tot;
+  const int amb_base = amb_incl - c_amb;
+  const int need = k - n_sure;  // 1 <= need <= n_amb by construction of the band around the k-th key
+  const uint16_t* q_h = q + slot * kD;
+  const uint16_t* rows = S + (P.sum_base[(int64_t)b * P.n_kv_heads + j] + geo.n_sink) * (int64_t)(2 * kD);
+
+  if (need < n_amb && n_amb > kAmbCap) {
+    // Fallback: exact fp64 scores for every candidate, then an exact 64-bit radix select.
+    uint64_t* kh = keys64 + slot * P.nb_stride + geo.n_sink;
+    for (int r = wave; r < n; r += 4) {
+      const double s = exact_score_wave<kD>(q_h, rows + (int64_t)r * 2 * kD, lane);
+      if (lane == 0) kh[r] = ordered_key64(s);
+    }
+    __threadfence_block();
+    __syncthreads();
+    uint64_t kth64;
+    int krem64;
+    radix_select<uint64_t>([&](int r) { return kh[r]; }, n, k, hist, scan_scratch, s_pair, kth64, krem64);
+    int run_sel = 0, run_eq = 0;
+    for (int base = 0; base < n; base += 256) {
+      const int r = base + tid;
+      const uint64_t key64 = r < n ? kh[r] : 0ull;
+      const bool gt = r < n && key64 > kth64;
+      const bool eq = r < n && key64 == kth64;
+      int tot_eq, tot_sel;
+      const int eq_before = run_eq + block_excl_count(eq, count_a, tot_eq);
+      const bool sel = gt || (eq && eq_before < krem64);
+      const int pos = run_sel + block_excl_count(sel, count_b, tot_sel);
+      if (sel && pos < P.k_max) out[pos] = geo.n_sink + r;
+      run_eq += tot_eq;
+      run_sel += tot_sel;
+    }
+    for (int r = k + tid; r < P.k_max; r += 256) out[r] = -1;
+    return;
+  }
+
+  const bool resolve = need < n_amb;  // otherwise every band candidate is kept and no exact score is needed
+  if (resolve) {
+    int a = amb_base;
+#pragma unroll
+    for (int i = 0; i < KPT; ++i)
+      if (key[i] >= lo_key && key[i] <= hi_key) amb_idx[a++] = r0 + i;
+    __syncthreads();
+    for (int e = wave; e < n_amb; e += 4) {
+      const double s = exact_score_wave<kD>(q_h, rows + (int64_t)amb_idx[e] * 2 * kD, lane);
+      if (lane == 0) amb_key[e] = ordered_key64(s);
+    }
+    __syncthreads();
+    if (tid < n_amb) {
+      const uint64_t mine = amb_key[tid];
+      int rank = 0;
+      for (int e = 0; e < n_amb; ++e) {
+        const uint64_t other = amb_key[e];
+        rank += (other > mine) || (other == mine && e < tid);
+      }
+      amb_chosen[tid] = rank < need;
+    }
+    __syncthreads();
+  }
+
+  // ordered compaction of the kept candidates
+  int c_sel = 0;
+  uint32_t sel_bits = 0;
+  {
+    int a = amb_base;
+#pragma unroll
+    for (int i = 0; i < KPT; ++i) {
+      const bool sure = key[i] > hi_key;
+      const bool amb = key[i] >= lo_key && key[i] <= hi_key;
+      bool sel = sure;
+      if (amb) {
+        sel = !resolve || amb_chosen[a];
+        ++a;
+      }
+      sel_bits |= (uint32_t)sel << i;
+      c_sel += sel;
+    }
+  }
+  int pos = block_incl_scan(c_sel, scan_scratch) - c_sel;
+#pragma unroll
+  for (int i = 0; i < KPT; ++i)
+    if ((sel_bits >> i) & 1u) {
+      if (pos < P.k_max) out[pos] = geo.n_sink + r0 + i;
+      ++pos;
+    }
+  for (int r = k + tid; r < P.k_max; r += 256) out[r] = -1;
+}
+
 float select_error_gamma() { return kGamma; }
 
 hipError_t launch_select(const Params& P, const void* q, const void* S, const float* budget_frac,
@@ -399,14 +616,26 @@ hipError_t launch_select(const Params& P, const void* q, const void* S, const fl
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   ScopedSlot prof(kSlotTopk, stream);
-  if (P.head_dim == 128)
-    hipLaunchKernelGGL(topk_kernel<128>, dim3(P.n_q_heads, P.batch), dim3(256), 0, stream, P, (const uint16_t*)q,
-                       (const uint16_t*)S, (const float*)approx, (const float*)mag, keys, budget_frac, budget_blocks,
-                       idx, cnt);
-  else
-    hipLaunchKernelGGL(topk_kernel<64>, dim3(P.n_q_heads, P.batch), dim3(256), 0, stream, P, (const uint16_t*)q,
-                       (const uint16_t*)S, (const float*)approx, (const float*)mag, keys, budget_frac, budget_blocks,
-                       idx, cnt);
+  const dim3 tgrid(P.n_q_heads, P.batch);
+#define FX_TOPK_ARGS                                                                                               \
+  P, (const uint16_t*)q, (const uint16_t*)S, (const float*)approx, (const float*)mag, keys, budget_frac, budget_blocks, \
+      idx, cnt
+#define FX_TOPK_REG(D, KPT) hipLaunchKernelGGL((topk_reg_kernel<D, KPT>), tgrid, dim3(256), 0, stream, FX_TOPK_ARGS)
+  if (P.head_dim == 128) {
+    if (P.nb_stride <= 1024) FX_TOPK_REG(128, 4);
+    else if (P.nb_stride <= 2048) FX_TOPK_REG(128, 8);
+    else if (P.nb_stride <= 4096) FX_TOPK_REG(128, 16);
+    else if (P.nb_stride <= 8192) FX_TOPK_REG(128, 32);
+    else hipLaunchKernelGGL(topk_kernel<128>, tgrid, dim3(256), 0, stream, FX_TOPK_ARGS);
+  } else {
+    if (P.nb_stride <= 1024) FX_TOPK_REG(64, 4);
+    else if (P.nb_stride <= 2048) FX_TOPK_REG(64, 8);
+    else if (P.nb_stride <= 4096) FX_TOPK_REG(64, 16);
+    else if (P.nb_stride <= 8192) FX_TOPK_REG(64, 32);
+    else hipLaunchKernelGGL(topk_kernel<64>, tgrid, dim3(256), 0, stream, FX_TOPK_ARGS);
+  }
+#undef FX_TOPK_REG
+#undef FX_TOPK_ARGS
   return hipGetLastError();
 }
 

@@ -35,6 +35,10 @@ def small_cases():
         "d128_g8_gran128": W.Workload(
             name="d", n_q_heads=8, n_kv_heads=1, head_dim=128, seq_len=[6000], gran=[128],
             sink_tokens=64, window_tokens=256, budget_frac=np.full((1, 8), 0.2, dtype=np.float32), seed=4),
+        "long_context_generic_topk": W.Workload(
+            name="f", n_q_heads=2, n_kv_heads=1, head_dim=64, seq_len=[140000, 20000], gran=[16],
+            sink_tokens=64, window_tokens=256, budget_frac=np.array([[0.03, 0.2], [0.5, 0.01]], dtype=np.float32),
+            seed=6),
         "mha_g1": W.Workload(
             name="e", n_q_heads=3, n_kv_heads=3, head_dim=128, seq_len=[1500, 900], gran=[16, 32, 80],
             sink_tokens=64, window_tokens=256, budget_frac=np.full((2, 3), 0.15, dtype=np.float32), seed=5),
