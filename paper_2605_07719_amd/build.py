@@ -9,17 +9,17 @@ LIB = os.path.join(HERE, "libfluxion.so")
 SOURCES = ["api.hip", "summarize.hip", "select.hip", "decode.hip", "probe.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-gpu-rdc",
-    # packed-fp32 VALU forms stay off (see the build notes in the design doc)
+    # packed-fp32 VALU forms stay off: hipcc must not turn float code into v_pk_*_f32
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
 ]
 
 
-def build(extra=()) -> str:
+def build(extra=(), out=LIB) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *FLAGS, *extra, "-o", LIB, *[os.path.join(CSRC, s) for s in SOURCES]]
+    cmd = [hipcc, *FLAGS, *extra, "-o", out, *[os.path.join(CSRC, s) for s in SOURCES]]
     subprocess.run(cmd, check=True)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

@@ -71,6 +71,8 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
   constexpr int kLanes = kD / 8;        // lanes that share one token row
   constexpr int kTPL = 64 / kLanes;     // token rows per wave-wide load
   constexpr int kLoads = 16 / kTPL;     // loads per 16-token slice
+  // register budget: prefetching pays only where it does not cost a resident wave (measured)
+  constexpr bool kPrefetch = kD == 128 ? (kG == 6 || kG == 7) : (kG >= 7);
   extern __shared__ int s_prefix[];     // [n_groups + 1] exclusive prefix of items per group
   __shared__ float s_red[4][kG][kD + 2];
   __shared__ int s_scan[4];
@@ -156,8 +158,9 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
       l_run[r] = 0.f;
     }
 
-    // Software pipeline: the K/V rows of the wave's next slice are requested before the current
-    // slice is consumed, so every wave always has one slice (8 KiB at d = 128) in flight.
+    // With kPrefetch the K/V rows of the wave's next slice are requested before the current slice is
+    // consumed (one slice, 8 KiB at d = 128, always in flight per wave) at the price of 32 registers;
+    // without it the kernel relies on more resident waves per SIMD.
     uint4 kraw[kLoads], vraw[kLoads], knext[kLoads], vnext[kLoads];
     uint32_t mask_next = 0;
     int t0_next = 0;
@@ -172,17 +175,21 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
         vr[i] = *reinterpret_cast<const uint4*>(Vb + row);
       }
     };
-    if (wave < n_slices) issue(wave, knext, vnext, mask_next, t0_next);
+    if (kPrefetch && wave < n_slices) issue(wave, knext, vnext, mask_next, t0_next);
 
     for (int sl = wave; sl < n_slices; sl += 4) {
+      if (kPrefetch) {
+#pragma unroll
+        for (int i = 0; i < kLoads; ++i) {
+          kraw[i] = knext[i];
+          vraw[i] = vnext[i];
+        }
+      } else {
+        issue(sl, kraw, vraw, mask_next, t0_next);
+      }
       const uint32_t mask = mask_next;
       const int t0 = t0_next;
-#pragma unroll
-      for (int i = 0; i < kLoads; ++i) {
-        kraw[i] = knext[i];
-        vraw[i] = vnext[i];
-      }
-      if (sl + 4 < n_slices) issue(sl + 4, knext, vnext, mask_next, t0_next);
+      if (kPrefetch && sl + 4 < n_slices) issue(sl + 4, knext, vnext, mask_next, t0_next);
 
       // logits (log2 domain) of the slice's tokens for every head that wants this block
       float sp[kG][kLoads];

@@ -30,9 +30,15 @@ inline SelectWorkspace carve_select(const Params& P) {
 
 // Split sizing of the decode stage.  A work item is one chunk of one group's union list; the chunk
 // length in tokens is 64 << s with the smallest s in [0, 4] that keeps the item count near kTargetItems.
+#ifndef FX_MAX_CHUNK_SHIFT
+#define FX_MAX_CHUNK_SHIFT 4
+#endif
+#ifndef FX_TARGET_ITEMS
+#define FX_TARGET_ITEMS 4096
+#endif
 constexpr int kMinChunkTokens = 64;
-constexpr int kMaxChunkShift = 4;
-constexpr int kTargetItems = 4096;
+constexpr int kMaxChunkShift = FX_MAX_CHUNK_SHIFT;
+constexpr int kTargetItems = FX_TARGET_ITEMS;
 constexpr int kMaxGroups = 4096;
 constexpr int kMaxChunkEntries = (kMinChunkTokens << kMaxChunkShift) / 16;  // smallest block is 16 tokens
 

@@ -32,6 +32,10 @@ typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 // measured error of every candidate against this bound.
 constexpr float kGamma = 1.0f / 16384.0f;
 constexpr int kAmbCap = 256;  // band candidates re-scored in LDS; more => fallback
+#ifndef FX_SCORE_TILES
+#define FX_SCORE_TILES 2
+#endif
+constexpr int kScoreTilesPerWave = FX_SCORE_TILES;  // tiles of 16 candidates a wave walks through
 
 __device__ __forceinline__ uint64_t ordered_key64(double s) {
   uint64_t u = (uint64_t)__double_as_longlong(s);
@@ -53,13 +57,15 @@ __device__ __forceinline__ float key32_to_float(uint32_t k) {
 // Here n = candidate within a tile of 16, k = position in the [mn | mx] row, and the A rows are
 //   m = 0..7 : [q- | q+] of head m of the group      (-> s~, from B)
 //   m = 8..15: [|q-| | |q+|] of head m - 8            (-> a~, from |B|)
+// The summaries are loaded straight into the B layout (each lane 16 bytes of its own row).  Staging
+// them through LDS with fully coalesced loads was measured to be about twice slower.
 template <int kD>
 __global__ __launch_bounds__(256) void score_kernel(Params P, const uint16_t* __restrict__ q,
                                                     const uint16_t* __restrict__ S, float* __restrict__ approx,
                                                     float* __restrict__ mag) {
   constexpr int kRow = 2 * kD;       // elements of one [mn | mx] row
   constexpr int kSlabs = kRow / 32;  // MFMA k-steps per row
-  constexpr int kTilesPerWave = 2;
+  constexpr int kTilesPerWave = kScoreTilesPerWave;
   const int b = blockIdx.z, j = blockIdx.y;
   const Geo geo = geometry(P, b, j);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -604,7 +610,7 @@ hipError_t launch_select(const Params& P, const void* q, const void* S, const fl
   uint64_t* keys = reinterpret_cast<uint64_t*>(ws + W.keys_off);
   {
     ScopedSlot prof(kSlotScore, stream);
-    const int cand_per_wg = 4 * 2 * 16;  // 4 waves x 2 tiles x 16 candidates
+    const int cand_per_wg = 4 * kScoreTilesPerWave * 16;  // 4 waves x tiles x 16 candidates
     dim3 sgrid((P.nb_stride + cand_per_wg - 1) / cand_per_wg, P.n_kv_heads, P.batch);
     if (P.head_dim == 128)
       hipLaunchKernelGGL(score_kernel<128>, sgrid, dim3(256), 0, stream, P, (const uint16_t*)q, (const uint16_t*)S,

@@ -15,7 +15,7 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libfluxion.so")
+LIB_PATH = os.environ.get("FLUXION_LIB", os.path.join(_HERE, "libfluxion.so"))  # override: development builds
 
 EXPORTS = (
     "fx_status_string", "fx_summarize", "fx_select_workspace_bytes", "fx_select", "fx_decode_workspace_bytes",
