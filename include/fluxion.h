@@ -80,6 +80,17 @@ typedef struct fx_layout {
  * Errors: INVALID_ARG (null/misaligned), UNSUPPORTED (layout outside the supported range), HIP. */
 fx_status fx_summarize(const fx_layout* layout, const void* K, void* summaries, void* stream);
 
+/* Incremental summaries for a cache that grew (decode appends tokens; blocks fill up and leave the local
+ * window, where selection starts to need their summaries).  Recomputes, for every (b, j), only the blocks
+ * that hold tokens at or after prev_len[b]; seq_len[b] is the length after the append.  The result equals
+ * fx_summarize on the grown cache provided the summaries of the blocks before prev_len[b] were up to date.
+ *   prev_len        DEVICE int32 [batch]: length of each sequence before the append (<= seq_len[b])
+ *   max_new_tokens  HOST bound on seq_len[b] - prev_len[b]; blocks beyond ceil(max_new_tokens/16) + 1 per
+ *                   (b, j), counted from the block holding token prev_len[b], are not revisited
+ * Errors: INVALID_ARG, UNSUPPORTED, HIP. */
+fx_status fx_summarize_append(const fx_layout* layout, const void* K, void* summaries, const int32_t* prev_len,
+                              int32_t max_new_tokens, void* stream);
+
 /* Bytes of scratch fx_select needs for this layout (HOST computation, depends on batch, n_q_heads,
  * max_seq_len and gran only).  Returns 0 if the layout is invalid. */
 size_t fx_select_workspace_bytes(const fx_layout* layout);
@@ -139,6 +150,43 @@ size_t fx_decode_workspace_bytes(const fx_layout* layout, int32_t k_max, int32_t
 fx_status fx_sparse_decode(const fx_layout* layout, const void* q, const void* K, const void* V, const int32_t* idx,
                            const int32_t* cnt, int32_t k_max, int32_t sink_tokens, int32_t window_tokens, float* out,
                            void* workspace, size_t workspace_bytes, void* stream);
+
+/* Group-union variant of fx_sparse_decode: every query head of a GQA group attends to the union of the blocks
+ * chosen by the heads of its group (plus sink and window).  The group's blocks are in registers for all its
+ * heads anyway (Sec. 5.3 bounds a group's data volume by the sum of its heads' budgets because the union is
+ * what is actually moved), so the extra tokens cost arithmetic but no extra HBM traffic.  Same arguments,
+ * workspace and errors as fx_sparse_decode. */
+fx_status fx_sparse_decode_union(const fx_layout* layout, const void* q, const void* K, const void* V,
+                                 const int32_t* idx, const int32_t* cnt, int32_t k_max, int32_t sink_tokens,
+                                 int32_t window_tokens, float* out, void* workspace, size_t workspace_bytes,
+                                 void* stream);
+
+/* Granularity-budget selector (Sec. 5.2 Eq. 1: bgt_h(blk) = bgt0_h + k_h * log2(blk); Sec. 5.3 Eq. 3: the data
+ * volume of a GQA group at block size blk is V(blk) = 2 * L_cpu / blk + 2 * L_cpu * sum_h bgt_h(blk), metadata
+ * plus selected KV, counted in keys).  HOST control logic, all pointers are HOST pointers.  For every KV head
+ * the candidate block size with the smallest V is chosen (ties: the earlier candidate) and every head's budget
+ * follows from Eq. 1 at that size, clipped to [0, 1].  Streaming heads (Sec. 3.2) get budget 0 and add nothing
+ * to V; a group made of streaming heads only keeps candidates[0] and reports V = 0 (it is not scheduled).
+ *   bgt0, slope   float [n_q_heads]: predicted head properties (budget at block size 1, growth per log2 block)
+ *   streaming     uint8 [n_q_heads] or NULL (no streaming heads): non-zero marks a streaming head
+ *   l_cpu         number of keys selection runs over (the candidate tokens)
+ *   candidates    int32 [n_candidates], e.g. {16, 32, 64, 128}
+ *   gran          int32 [n_kv_heads], written;  budget float [n_q_heads], written (feeds fx_select's budget_frac)
+ *   volume        double [n_kv_heads] or NULL, written: V at the chosen size (the task priority of Sec. 6.2)
+ * Errors: INVALID_ARG. */
+fx_status fx_choose_granularity(int32_t n_q_heads, int32_t n_kv_heads, const float* bgt0, const float* slope,
+                                const uint8_t* streaming, int64_t l_cpu, const int32_t* candidates,
+                                int32_t n_candidates, int32_t* gran, float* budget, double* volume);
+
+/* Summary pyramid: summaries of a coarser block size from finer ones, exactly (a block of r*g tokens is r
+ * blocks of g tokens, so its minimum row is the minimum of their minimum rows and likewise for the maximum).
+ * `fine` and `coarse` describe the same sequences (equal seq_len contents) and differ only in gran[] and
+ * sum_base[]; coarse->gran[j] must be
+ * a multiple of fine->gran[j] (both valid block sizes).  Reads 1/g of what fx_summarize reads.  The result is
+ * identical to fx_summarize run with `coarse`.
+ * Errors: INVALID_ARG (null/misaligned, layouts that differ in shape), UNSUPPORTED, HIP. */
+fx_status fx_coarsen_summaries(const fx_layout* fine, const void* fine_summaries, const fx_layout* coarse,
+                               void* coarse_summaries, void* stream);
 
 /* Measurement aid (not part of the method).  While enabled, fx_select and fx_sparse_decode bracket every
  * kernel they launch with HIP events recorded on the caller's stream; fx_profile_read waits for the

@@ -134,18 +134,22 @@ int64_t budget_to_k(const float* budget_frac, const int32_t* budget_blocks, int6
 
 // Tokens head h of sequence b attends to: valid tokens of its selected blocks, of the sink blocks and
 // of the window blocks, in ascending order, each once.
+// With group_union the selected blocks of every head of h's GQA group count (Sec. 5.3 discusses the
+// union of a group's selections as the data that is actually moved).
 std::vector<int64_t> token_set(const Layout& L, int b, int h, const int32_t* idx, const int32_t* cnt,
-                               int k_max, int sink_tokens, int window_tokens) {
+                               int k_max, int sink_tokens, int window_tokens, bool group_union = false) {
   int G = L.n_q_heads / L.n_kv_heads;
   int j = h / G;
   Geometry geo = geometry(L, b, j, sink_tokens, window_tokens);
   std::vector<char> keep(static_cast<size_t>(geo.n_blocks), 0);
   for (int64_t i = 0; i < geo.n_blocks; ++i)
     if (i < geo.n_sink || i >= geo.w0) keep[i] = 1;
-  int64_t slot = static_cast<int64_t>(b) * L.n_q_heads + h;
-  for (int r = 0; r < cnt[slot]; ++r) {
-    int64_t i = idx[slot * k_max + r];
-    if (i >= 0 && i < geo.n_blocks) keep[i] = 1;
+  for (int hh = group_union ? j * G : h; hh < (group_union ? (j + 1) * G : h + 1); ++hh) {
+    int64_t slot = static_cast<int64_t>(b) * L.n_q_heads + hh;
+    for (int r = 0; r < cnt[slot]; ++r) {
+      int64_t i = idx[slot * k_max + r];
+      if (i >= 0 && i < geo.n_blocks) keep[i] = 1;
+    }
   }
   std::vector<int64_t> tokens;
   for (int64_t i = 0; i < geo.n_blocks; ++i) {
@@ -335,17 +339,18 @@ int fxo_select(const fxo_layout* l, const uint16_t* q, const uint16_t* S, const 
 
 // Sparse attention of every head over its own token set (App. A.1 restricted to the kept tokens).
 // mode 0: two-pass softmax.  mode 1: split into chunks of `chunk_tokens` and merged.
+// group_union != 0: every head attends to the union of its group's selections.
 // out[(b*Hq+h)*d + c] in fp64; lse (optional) [b*Hq+h], mode 0 only.
 void fxo_sparse_attention(const fxo_layout* l, const uint16_t* q, const uint16_t* K, const uint16_t* V,
                           const int32_t* idx, const int32_t* cnt, int k_max, int sink_tokens, int window_tokens,
-                          int mode, int64_t chunk_tokens, double* out, double* lse, int n_threads) {
+                          int mode, int64_t chunk_tokens, int group_union, double* out, double* lse, int n_threads) {
   Layout L = to_layout(l);
   int G = L.n_q_heads / L.n_kv_heads;
   int64_t n_tasks = static_cast<int64_t>(L.batch) * L.n_q_heads;
   parallel_for(n_tasks, n_threads, [&](int64_t task) {
     int b = static_cast<int>(task / L.n_q_heads), h = static_cast<int>(task % L.n_q_heads);
     int j = h / G;
-    std::vector<int64_t> tokens = token_set(L, b, h, idx, cnt, k_max, sink_tokens, window_tokens);
+    std::vector<int64_t> tokens = token_set(L, b, h, idx, cnt, k_max, sink_tokens, window_tokens, group_union != 0);
     const uint16_t* q_h = q + task * L.head_dim;
     if (mode == 0)
       attend_two_pass(L, q_h, K, V, b, j, tokens, out + task * L.head_dim, nullptr, lse ? lse + task : nullptr);
@@ -374,10 +379,11 @@ void fxo_dense_attention(const fxo_layout* l, const uint16_t* q, const uint16_t*
 // tokens/weights and returns the size of the set.
 int64_t fxo_token_weights(const fxo_layout* l, const uint16_t* q, const uint16_t* K, const uint16_t* V,
                           const int32_t* idx, const int32_t* cnt, int k_max, int sink_tokens, int window_tokens,
-                          int b, int h, int64_t capacity, int64_t* tokens_out, double* weights_out) {
+                          int b, int h, int group_union, int64_t capacity, int64_t* tokens_out,
+                          double* weights_out) {
   Layout L = to_layout(l);
   int G = L.n_q_heads / L.n_kv_heads;
-  std::vector<int64_t> tokens = token_set(L, b, h, idx, cnt, k_max, sink_tokens, window_tokens);
+  std::vector<int64_t> tokens = token_set(L, b, h, idx, cnt, k_max, sink_tokens, window_tokens, group_union != 0);
   std::vector<double> w(tokens.size()), o(static_cast<size_t>(L.head_dim));
   int64_t task = static_cast<int64_t>(b) * L.n_q_heads + h;
   attend_two_pass(L, q + task * L.head_dim, K, V, b, h / G, tokens, o.data(), w.data(), nullptr);
@@ -396,7 +402,7 @@ int fxo_layer_step(const fxo_layout* l, const uint16_t* q, const uint16_t* K, co
   int rc = fxo_select(l, q, S, budget_frac, budget_blocks, sink_tokens, window_tokens, k_max, idx, cnt, nullptr,
                       nullptr, n_threads);
   if (rc != 0) return rc;
-  fxo_sparse_attention(l, q, K, V, idx, cnt, k_max, sink_tokens, window_tokens, 0, 0, out, nullptr, n_threads);
+  fxo_sparse_attention(l, q, K, V, idx, cnt, k_max, sink_tokens, window_tokens, 0, 0, 0, out, nullptr, n_threads);
   return 0;
 }
 

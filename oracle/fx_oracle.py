@@ -161,7 +161,7 @@ def select(L: OracleLayout, q, S, *, budget_frac=None, budget_blocks=None, sink_
 
 
 def sparse_attention(L: OracleLayout, q, K, V, idx, cnt, *, sink_tokens: int, window_tokens: int, mode: str = "two_pass",
-                     chunk_tokens: int = 0, threads: int = 1, return_lse: bool = False):
+                     chunk_tokens: int = 0, threads: int = 1, return_lse: bool = False, group_union: bool = False):
     q, K, V = _u16(q), _u16(K), _u16(V)
     idx = np.ascontiguousarray(idx, dtype=np.int32)
     cnt = np.ascontiguousarray(cnt, dtype=np.int32)
@@ -175,7 +175,7 @@ def sparse_attention(L: OracleLayout, q, K, V, idx, cnt, *, sink_tokens: int, wi
     _load().fxo_sparse_attention(
         ctypes.byref(c), _ptr(q), _ptr(K), _ptr(V), _ptr(idx), _ptr(cnt), ctypes.c_int(k_max),
         ctypes.c_int(sink_tokens), ctypes.c_int(window_tokens), ctypes.c_int(m), ctypes.c_int64(chunk_tokens),
-        _ptr(out), _ptr(lse), ctypes.c_int(threads),
+        ctypes.c_int(1 if group_union else 0), _ptr(out), _ptr(lse), ctypes.c_int(threads),
     )
     return (out, lse) if return_lse else out
 
@@ -189,7 +189,8 @@ def dense_attention(L: OracleLayout, q, K, V, threads: int = 1, return_lse: bool
     return (out, lse) if return_lse else out
 
 
-def token_weights(L: OracleLayout, q, K, V, idx, cnt, *, sink_tokens: int, window_tokens: int, b: int, h: int):
+def token_weights(L: OracleLayout, q, K, V, idx, cnt, *, sink_tokens: int, window_tokens: int, b: int, h: int,
+                  group_union: bool = False):
     """Token set of head (b, h) and its softmax weights (two-pass)."""
     q, K, V = _u16(q), _u16(K), _u16(V)
     idx = np.ascontiguousarray(idx, dtype=np.int32)
@@ -201,7 +202,7 @@ def token_weights(L: OracleLayout, q, K, V, idx, cnt, *, sink_tokens: int, windo
     n = _load().fxo_token_weights(
         ctypes.byref(c), _ptr(q), _ptr(K), _ptr(V), _ptr(idx), _ptr(cnt), ctypes.c_int(idx.shape[-1]),
         ctypes.c_int(sink_tokens), ctypes.c_int(window_tokens), ctypes.c_int(b), ctypes.c_int(h),
-        ctypes.c_int64(cap), _ptr(tokens), _ptr(w),
+        ctypes.c_int(1 if group_union else 0), ctypes.c_int64(cap), _ptr(tokens), _ptr(w),
     )
     return tokens[:n].copy(), w[:n].copy()
 

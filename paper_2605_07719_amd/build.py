@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfluxion.so")
-SOURCES = ["api.hip", "summarize.hip", "select.hip", "decode.hip", "probe.hip"]
+SOURCES = ["api.hip", "summarize.hip", "select.hip", "decode.hip", "probe.hip", "selector.cpp"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-gpu-rdc",
     # packed-fp32 VALU forms stay off: hipcc must not turn float code into v_pk_*_f32

@@ -47,6 +47,7 @@ fx_status make_params(const fx_layout* L, int32_t sink_tokens, int32_t window_to
   P->sink_tokens = sink_tokens;
   P->window_tokens = window_tokens;
   P->k_max = k_max;
+  P->group_union = 0;
   return FX_OK;
 }
 
@@ -122,7 +123,44 @@ fx_status fx_summarize(const fx_layout* layout, const void* K, void* summaries, 
   if (st != FX_OK) return st;
   if (!K || !summaries || !aligned16(K) || !aligned16(summaries)) return FX_ERR_INVALID_ARG;
   if (P.max_seq_len == 0) return FX_OK;
-  return fx::launch_summarize(P, K, summaries, static_cast<hipStream_t>(stream)) == hipSuccess ? FX_OK : FX_ERR_HIP;
+  return fx::launch_summarize(P, K, summaries, nullptr, 0, static_cast<hipStream_t>(stream)) == hipSuccess
+             ? FX_OK
+             : FX_ERR_HIP;
+}
+
+fx_status fx_summarize_append(const fx_layout* layout, const void* K, void* summaries, const int32_t* prev_len,
+                              int32_t max_new_tokens, void* stream) {
+  fx::Params P;
+  fx_status st = make_params(layout, 0, 0, 1, &P);
+  if (st != FX_OK) return st;
+  if (!K || !summaries || !prev_len || !aligned16(K) || !aligned16(summaries) || max_new_tokens < 0)
+    return FX_ERR_INVALID_ARG;
+  if (P.max_seq_len == 0) return FX_OK;
+  if (max_new_tokens > P.max_seq_len) max_new_tokens = P.max_seq_len;
+  return fx::launch_summarize(P, K, summaries, prev_len, max_new_tokens, static_cast<hipStream_t>(stream)) ==
+                 hipSuccess
+             ? FX_OK
+             : FX_ERR_HIP;
+}
+
+fx_status fx_coarsen_summaries(const fx_layout* fine, const void* fine_summaries, const fx_layout* coarse,
+                               void* coarse_summaries, void* stream) {
+  fx::Params Pf, Pc;
+  fx_status st = make_params(fine, 0, 0, 1, &Pf);
+  if (st != FX_OK) return st;
+  st = make_params(coarse, 0, 0, 1, &Pc);
+  if (st != FX_OK) return st;
+  if (!fine_summaries || !coarse_summaries || !aligned16(fine_summaries) || !aligned16(coarse_summaries))
+    return FX_ERR_INVALID_ARG;
+  if (Pf.batch != Pc.batch || Pf.n_q_heads != Pc.n_q_heads || Pf.n_kv_heads != Pc.n_kv_heads ||
+      Pf.head_dim != Pc.head_dim || Pf.max_seq_len != Pc.max_seq_len)
+    return FX_ERR_INVALID_ARG;
+  for (int j = 0; j < Pf.n_kv_heads; ++j)
+    if (Pc.gran[j] % Pf.gran[j] != 0) return FX_ERR_INVALID_ARG;
+  if (Pc.max_seq_len == 0) return FX_OK;
+  return fx::launch_coarsen(Pf, Pc, fine_summaries, coarse_summaries, static_cast<hipStream_t>(stream)) == hipSuccess
+             ? FX_OK
+             : FX_ERR_HIP;
 }
 
 size_t fx_select_workspace_bytes(const fx_layout* layout) {
@@ -167,19 +205,36 @@ size_t fx_decode_workspace_bytes(const fx_layout* layout, int32_t k_max, int32_t
   return fx::carve_decode(P).total;
 }
 
-fx_status fx_sparse_decode(const fx_layout* layout, const void* q, const void* K, const void* V, const int32_t* idx,
-                           const int32_t* cnt, int32_t k_max, int32_t sink_tokens, int32_t window_tokens, float* out,
-                           void* workspace, size_t workspace_bytes, void* stream) {
+static fx_status sparse_decode_impl(const fx_layout* layout, const void* q, const void* K, const void* V,
+                                    const int32_t* idx, const int32_t* cnt, int32_t k_max, int32_t sink_tokens,
+                                    int32_t window_tokens, float* out, void* workspace, size_t workspace_bytes,
+                                    void* stream, int group_union) {
   fx::Params P;
   fx_status st = make_params(layout, sink_tokens, window_tokens, k_max, &P);
   if (st != FX_OK) return st;
   if (!q || !K || !V || !idx || !cnt || !out || !workspace) return FX_ERR_INVALID_ARG;
   if (!aligned16(q) || !aligned16(K) || !aligned16(V) || !aligned16(workspace)) return FX_ERR_INVALID_ARG;
   if (workspace_bytes < fx::carve_decode(P).total) return FX_ERR_WORKSPACE_TOO_SMALL;
+  P.group_union = group_union;
   return fx::launch_decode(P, q, K, V, idx, cnt, out, workspace, compute_units(), static_cast<hipStream_t>(stream)) ==
                  hipSuccess
              ? FX_OK
              : FX_ERR_HIP;
+}
+
+fx_status fx_sparse_decode(const fx_layout* layout, const void* q, const void* K, const void* V, const int32_t* idx,
+                           const int32_t* cnt, int32_t k_max, int32_t sink_tokens, int32_t window_tokens, float* out,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+  return sparse_decode_impl(layout, q, K, V, idx, cnt, k_max, sink_tokens, window_tokens, out, workspace,
+                            workspace_bytes, stream, 0);
+}
+
+fx_status fx_sparse_decode_union(const fx_layout* layout, const void* q, const void* K, const void* V,
+                                 const int32_t* idx, const int32_t* cnt, int32_t k_max, int32_t sink_tokens,
+                                 int32_t window_tokens, float* out, void* workspace, size_t workspace_bytes,
+                                 void* stream) {
+  return sparse_decode_impl(layout, q, K, V, idx, cnt, k_max, sink_tokens, window_tokens, out, workspace,
+                            workspace_bytes, stream, 1);
 }
 
 }  // extern "C"

@@ -44,21 +44,29 @@ __global__ __launch_bounds__(256) void plan_kernel(Params P, const int32_t* __re
     }
   }
   __syncthreads();
+  // ordered compaction: thread t owns the consecutive blocks [t * per, (t + 1) * per), so one block
+  // scan of the per-thread counts gives every thread its write position
   const uint32_t all = (1u << P.group) - 1u;
-  int run = 0;
-  for (int base = 0; base < geo.n_blocks; base += 256) {
-    const int i = base + tid;
-    uint32_t m = 0;
-    if (i < geo.n_blocks) {
-      m = (mask_words[i >> 2] >> ((i & 3) * 8)) & 255u;
-      if (i < geo.n_sink || i >= geo.w0) m = all;
+  const int per = (geo.n_blocks + 255) >> 8;
+  const int i0 = min(tid * per, geo.n_blocks), i1 = min(i0 + per, geo.n_blocks);
+  auto mask_of = [&](int i) -> uint32_t {
+    if (i < geo.n_sink || i >= geo.w0) return all;
+    const uint32_t m = (mask_words[i >> 2] >> ((i & 3) * 8)) & 255u;
+    return (P.group_union && m) ? all : m;
+  };
+  int mine = 0;
+  for (int i = i0; i < i1; ++i) mine += mask_of(i) != 0u;
+  const int incl = block_incl_scan(mine, scratch);
+  int pos = incl - mine;
+  uint32_t* dst = uni + (int64_t)grp * union_cap;
+  for (int i = i0; i < i1; ++i) {
+    const uint32_t m = mask_of(i);
+    if (m != 0u) {
+      if (pos < union_cap) dst[pos] = ((uint32_t)i << 8) | m;
+      ++pos;
     }
-    int tot;
-    const int pos = run + block_excl_count(m != 0, scratch, tot);
-    if (m != 0 && pos < union_cap) uni[(int64_t)grp * union_cap + pos] = ((uint32_t)i << 8) | m;
-    run += tot;
   }
-  if (tid == 0) ucount[grp] = run < union_cap ? run : union_cap;
+  if (tid == 255) ucount[grp] = incl < union_cap ? incl : union_cap;
 }
 
 template <int kD, int kG>
@@ -298,8 +306,7 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
 
 // One workgroup per (sequence, query head).  Pass 1 finds the global maximum over the group's items;
 // pass 2 spreads the items over 256 / (kD/4) slices of threads, each thread owning 4 channels, and adds
-// acc * 2^(m - M) (items whose sum is zero -- the head was not in the item's masks -- are skipped);
-// the slices are then summed in a fixed order.
+// acc * 2^(m - M); the slices are then summed in a fixed order.
 template <int kD>
 __global__ __launch_bounds__(256) void merge_kernel(Params P, const int32_t* __restrict__ sched,
                                                     const float* __restrict__ acc_part,
@@ -326,14 +333,15 @@ __global__ __launch_bounds__(256) void merge_kernel(Params P, const int32_t* __r
   const int slice = tid / kLanesC, cl = tid % kLanesC;
   float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
   float L = 0.f;
+  // loads are unconditional (an item in which this head took no part contributes exact zeros), so
+  // the compiler can keep several iterations in flight
+#pragma unroll 4
   for (int it = p0 + slice; it < p1; it += kSlices) {
     const float2 ml = *reinterpret_cast<const float2*>(ml_part + ((int64_t)it * G + r) * 2);
-    if (ml.y > 0.f) {
-      const float w = __builtin_amdgcn_exp2f(ml.x - M);
-      const float4 a = *reinterpret_cast<const float4*>(acc_part + ((int64_t)it * G + r) * kD + cl * 4);
-      L += ml.y * w;
-      o.x += a.x * w; o.y += a.y * w; o.z += a.z * w; o.w += a.w * w;
-    }
+    const float4 a = *reinterpret_cast<const float4*>(acc_part + ((int64_t)it * G + r) * kD + cl * 4);
+    const float w = __builtin_amdgcn_exp2f(ml.x - M);
+    L += ml.y * w;
+    o.x += a.x * w; o.y += a.y * w; o.z += a.z * w; o.w += a.w * w;
   }
   *reinterpret_cast<float4*>(&s_o[slice][cl * 4]) = o;
   if (cl == 0) s_l[slice] = L;

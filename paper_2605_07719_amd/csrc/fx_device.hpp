@@ -22,6 +22,7 @@ struct Params {
   uint8_t gran[kMaxKvHeads];  // block size g_j of KV head j, in tokens (16..128)
   int32_t sink_tokens, window_tokens, k_max;
   int32_t nb_stride;  // row length of per-(b,h) block arrays: max over j of ceil(max_seq_len / g_j)
+  int32_t group_union;  // decode only: every head of a group attends to the union of the group's selections
 };
 
 // Block geometry of one (sequence, KV head): see the header of the C ABI.

@@ -105,7 +105,9 @@ struct ScopedSlot {  // records start on construction and stop on destruction, o
 };
 
 float select_error_gamma();
-hipError_t launch_summarize(const Params& P, const void* K, void* S, hipStream_t stream);
+hipError_t launch_summarize(const Params& P, const void* K, void* S, const int32_t* prev_len, int max_new_tokens,
+                            hipStream_t stream);
+hipError_t launch_coarsen(const Params& Pf, const Params& Pc, const void* Sf, void* Sc, hipStream_t stream);
 hipError_t launch_select(const Params& P, const void* q, const void* S, const float* budget_frac,
                          const int32_t* budget_blocks, int32_t* idx, int32_t* cnt, void* workspace,
                          hipStream_t stream);

@@ -62,7 +62,8 @@ __device__ __forceinline__ float key32_to_float(uint32_t k) {
 template <int kD>
 __global__ __launch_bounds__(256) void score_kernel(Params P, const uint16_t* __restrict__ q,
                                                     const uint16_t* __restrict__ S, float* __restrict__ approx,
-                                                    float* __restrict__ mag) {
+                                                    float* __restrict__ mag, const float* __restrict__ budget_frac,
+                                                    const int32_t* __restrict__ budget_blocks) {
   constexpr int kRow = 2 * kD;       // elements of one [mn | mx] row
   constexpr int kSlabs = kRow / 32;  // MFMA k-steps per row
   constexpr int kTilesPerWave = kScoreTilesPerWave;
@@ -72,6 +73,16 @@ __global__ __launch_bounds__(256) void score_kernel(Params P, const uint16_t* __
   const int n = lane & 15, r = lane >> 4;
   const int tile_first = (blockIdx.x * 4 + wave) * kTilesPerWave;
   if (tile_first * 16 >= geo.n_cand) return;
+  {
+    // a group whose heads all have budget 0 (streaming heads, Sec. 3.2) needs no scores: its summaries
+    // are not read at all
+    bool any = false;
+    for (int h = 0; h < P.group; ++h) {
+      const int64_t slot = (int64_t)b * P.n_q_heads + j * P.group + h;
+      any |= budget_blocks ? budget_blocks[slot] > 0 : budget_frac[slot] > 0.f;
+    }
+    if (!any) return;
+  }
 
   // A operand, built once per wave from q
   uint4 a_op[kSlabs];
@@ -614,10 +625,10 @@ hipError_t launch_select(const Params& P, const void* q, const void* S, const fl
     dim3 sgrid((P.nb_stride + cand_per_wg - 1) / cand_per_wg, P.n_kv_heads, P.batch);
     if (P.head_dim == 128)
       hipLaunchKernelGGL(score_kernel<128>, sgrid, dim3(256), 0, stream, P, (const uint16_t*)q, (const uint16_t*)S,
-                         approx, mag);
+                         approx, mag, budget_frac, budget_blocks);
     else
       hipLaunchKernelGGL(score_kernel<64>, sgrid, dim3(256), 0, stream, P, (const uint16_t*)q, (const uint16_t*)S,
-                         approx, mag);
+                         approx, mag, budget_frac, budget_blocks);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

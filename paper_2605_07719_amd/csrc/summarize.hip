@@ -9,14 +9,21 @@
 
 namespace fx {
 
+// With `prev_len` (append mode) only the blocks that hold tokens at or after prev_len[b] are redone.
 template <int kD>
 __global__ __launch_bounds__(256) void summarize_kernel(Params P, const uint16_t* __restrict__ K,
-                                                        uint16_t* __restrict__ S) {
+                                                        uint16_t* __restrict__ S,
+                                                        const int32_t* __restrict__ prev_len) {
   constexpr int kLanes = kD / 8;         // lanes per token row
   constexpr int kBlocksPerWg = 256 / kLanes;
   const int b = blockIdx.z, j = blockIdx.y;
   const Geo geo = geometry(P, b, j);
-  const int i = blockIdx.x * kBlocksPerWg + threadIdx.x / kLanes;
+  int first_block = 0;
+  if (prev_len) {
+    const int p = prev_len[b];
+    first_block = (p < 0 ? 0 : p) / geo.g;
+  }
+  const int i = first_block + blockIdx.x * kBlocksPerWg + threadIdx.x / kLanes;
   if (i >= geo.n_blocks) return;
   const int chunk = threadIdx.x % kLanes;
   const int t_lo = i * geo.g;
@@ -47,14 +54,64 @@ __global__ __launch_bounds__(256) void summarize_kernel(Params P, const uint16_t
   *reinterpret_cast<uint4*>(dst + kD) = pack8(mx);
 }
 
-hipError_t launch_summarize(const Params& P, const void* K, void* S, hipStream_t stream) {
+// Summary pyramid: one coarse block = `ratio` consecutive fine blocks; same thread mapping as above,
+// reading summary rows instead of key rows.
+template <int kD>
+__global__ __launch_bounds__(256) void coarsen_kernel(Params Pf, Params Pc, const uint16_t* __restrict__ Sf,
+                                                      uint16_t* __restrict__ Sc) {
+  constexpr int kLanes = kD / 8;
+  constexpr int kBlocksPerWg = 256 / kLanes;
+  const int b = blockIdx.z, j = blockIdx.y;
+  const Geo gc = geometry(Pc, b, j);
+  const Geo gf = geometry(Pf, b, j);
+  const int i = blockIdx.x * kBlocksPerWg + threadIdx.x / kLanes;
+  if (i >= gc.n_blocks) return;
+  const int chunk = threadIdx.x % kLanes;
+  const int ratio = gc.g / gf.g;
+  const int f_lo = i * ratio;
+  const int f_hi = min(f_lo + ratio, gf.n_blocks);
+  const uint16_t* src = Sf + Pf.sum_base[(int64_t)b * Pf.n_kv_heads + j] * 2 * (int64_t)kD + chunk * 8;
+  float mn[8], mx[8];
+  unpack8(*reinterpret_cast<const uint4*>(src + (int64_t)f_lo * 2 * kD), mn);
+  unpack8(*reinterpret_cast<const uint4*>(src + (int64_t)f_lo * 2 * kD + kD), mx);
+  for (int f = f_lo + 1; f < f_hi; ++f) {
+    float a[8], c[8];
+    unpack8(*reinterpret_cast<const uint4*>(src + (int64_t)f * 2 * kD), a);
+    unpack8(*reinterpret_cast<const uint4*>(src + (int64_t)f * 2 * kD + kD), c);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      mn[t] = fminf(mn[t], a[t]);
+      mx[t] = fmaxf(mx[t], c[t]);
+    }
+  }
+  uint16_t* dst = Sc + (Pc.sum_base[(int64_t)b * Pc.n_kv_heads + j] + i) * 2 * (int64_t)kD + chunk * 8;
+  *reinterpret_cast<uint4*>(dst) = pack8(mn);
+  *reinterpret_cast<uint4*>(dst + kD) = pack8(mx);
+}
+
+hipError_t launch_coarsen(const Params& Pf, const Params& Pc, const void* Sf, void* Sc, hipStream_t stream) {
+  const int blocks_per_wg = 256 / (Pc.head_dim / 8);
+  dim3 grid((Pc.nb_stride + blocks_per_wg - 1) / blocks_per_wg, Pc.n_kv_heads, Pc.batch);
+  if (Pc.head_dim == 128)
+    hipLaunchKernelGGL(coarsen_kernel<128>, grid, dim3(256), 0, stream, Pf, Pc, (const uint16_t*)Sf, (uint16_t*)Sc);
+  else
+    hipLaunchKernelGGL(coarsen_kernel<64>, grid, dim3(256), 0, stream, Pf, Pc, (const uint16_t*)Sf, (uint16_t*)Sc);
+  return hipGetLastError();
+}
+
+hipError_t launch_summarize(const Params& P, const void* K, void* S, const int32_t* prev_len, int max_new_tokens,
+                            hipStream_t stream) {
   const int lanes = P.head_dim / 8;
   const int blocks_per_wg = 256 / lanes;
-  dim3 grid((P.nb_stride + blocks_per_wg - 1) / blocks_per_wg, P.n_kv_heads, P.batch);
+  // append mode: at most ceil(max_new / 16) + 1 blocks per (sequence, KV head) change
+  const int blocks = prev_len ? (max_new_tokens + 15) / 16 + 1 : P.nb_stride;
+  dim3 grid((blocks + blocks_per_wg - 1) / blocks_per_wg, P.n_kv_heads, P.batch);
   if (P.head_dim == 128)
-    hipLaunchKernelGGL(summarize_kernel<128>, grid, dim3(256), 0, stream, P, (const uint16_t*)K, (uint16_t*)S);
+    hipLaunchKernelGGL(summarize_kernel<128>, grid, dim3(256), 0, stream, P, (const uint16_t*)K, (uint16_t*)S,
+                       prev_len);
   else
-    hipLaunchKernelGGL(summarize_kernel<64>, grid, dim3(256), 0, stream, P, (const uint16_t*)K, (uint16_t*)S);
+    hipLaunchKernelGGL(summarize_kernel<64>, grid, dim3(256), 0, stream, P, (const uint16_t*)K, (uint16_t*)S,
+                       prev_len);
   return hipGetLastError();
 }
 

@@ -19,7 +19,8 @@ LIB_PATH = os.environ.get("FLUXION_LIB", os.path.join(_HERE, "libfluxion.so"))  
 
 EXPORTS = (
     "fx_status_string", "fx_summarize", "fx_select_workspace_bytes", "fx_select", "fx_decode_workspace_bytes",
-    "fx_sparse_decode", "fx_profile_enable", "fx_profile_read", "fx_probe_read", "fx_probe_copy", "fx_select_workspace_view",
+    "fx_sparse_decode", "fx_profile_enable", "fx_profile_read", "fx_probe_read", "fx_probe_copy", "fx_select_workspace_view", "fx_choose_granularity",
+    "fx_coarsen_summaries", "fx_summarize_append", "fx_sparse_decode_union",
 )
 
 FX_OK, FX_ERR_INVALID_ARG, FX_ERR_UNSUPPORTED, FX_ERR_WORKSPACE_TOO_SMALL, FX_ERR_HIP = range(5)
@@ -68,9 +69,12 @@ def lib() -> ctypes.CDLL:
         L.fx_select.restype = ctypes.c_int
         L.fx_select.argtypes = [ctypes.c_void_p] * 5 + [ctypes.c_int32] * 3 + [ctypes.c_void_p] * 3 + [
             ctypes.c_size_t, ctypes.c_void_p]
-        L.fx_sparse_decode.restype = ctypes.c_int
-        L.fx_sparse_decode.argtypes = [ctypes.c_void_p] * 6 + [ctypes.c_int32] * 3 + [ctypes.c_void_p] * 2 + [
-            ctypes.c_size_t, ctypes.c_void_p]
+        for fn in (L.fx_sparse_decode, L.fx_sparse_decode_union):
+            fn.restype = ctypes.c_int
+            fn.argtypes = [ctypes.c_void_p] * 6 + [ctypes.c_int32] * 3 + [ctypes.c_void_p] * 2 + [
+                ctypes.c_size_t, ctypes.c_void_p]
+        L.fx_summarize_append.restype = ctypes.c_int
+        L.fx_summarize_append.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_int32, ctypes.c_void_p]
         L.fx_profile_enable.restype = ctypes.c_int
         L.fx_profile_enable.argtypes = [ctypes.c_int]
         L.fx_profile_read.restype = ctypes.c_int
@@ -154,6 +158,38 @@ def select_workspace_bytes(layout: Layout) -> int:
     return int(lib().fx_select_workspace_bytes(ctypes.byref(c)))
 
 
+def choose_granularity(n_q_heads: int, n_kv_heads: int, bgt0, slope, l_cpu: int, streaming=None,
+                       candidates=(16, 32, 64, 128)):
+    """fx_choose_granularity: (gran int32 [Hkv], budget float32 [Hq], volume float64 [Hkv])."""
+    bgt0 = np.ascontiguousarray(bgt0, dtype=np.float32)
+    slope = np.ascontiguousarray(slope, dtype=np.float32)
+    assert bgt0.shape == (n_q_heads,) and slope.shape == (n_q_heads,)
+    st = None if streaming is None else np.ascontiguousarray(streaming, dtype=np.uint8)
+    cand = np.ascontiguousarray(candidates, dtype=np.int32)
+    gran = np.zeros(n_kv_heads, dtype=np.int32)
+    budget = np.zeros(n_q_heads, dtype=np.float32)
+    volume = np.zeros(n_kv_heads, dtype=np.float64)
+    fn = lib().fx_choose_granularity
+    fn.restype = ctypes.c_int
+    fn.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
+                   ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    _check(fn(n_q_heads, n_kv_heads, bgt0.ctypes.data, slope.ctypes.data, None if st is None else st.ctypes.data,
+              int(l_cpu), cand.ctypes.data, int(cand.size), gran.ctypes.data, budget.ctypes.data,
+              volume.ctypes.data), "fx_choose_granularity")
+    return gran, budget, volume
+
+
+def coarsen_summaries(fine: Layout, fine_summaries: torch.Tensor, coarse: Layout, coarse_summaries: torch.Tensor,
+                      stream=None) -> None:
+    """fx_coarsen_summaries: summaries at coarse.gran from summaries at fine.gran (exact)."""
+    cf, cc = fine.c_struct(), coarse.c_struct()
+    fn = lib().fx_coarsen_summaries
+    fn.restype = ctypes.c_int
+    fn.argtypes = [ctypes.c_void_p] * 5
+    _check(fn(ctypes.byref(cf), _dptr(fine_summaries), ctypes.byref(cc), _dptr(coarse_summaries), _stream(stream)),
+           "fx_coarsen_summaries")
+
+
 def select_workspace_view(layout: Layout) -> dict:
     """fx_select_workspace_view: byte offsets of the approximate scores and their error magnitudes."""
     c = layout.c_struct()
@@ -192,13 +228,24 @@ def select(layout: Layout, q: torch.Tensor, summaries: torch.Tensor, *, budget_f
     )
 
 
+def summarize_append(layout: Layout, K: torch.Tensor, summaries: torch.Tensor, prev_len: torch.Tensor,
+                     max_new_tokens: int, stream=None) -> None:
+    """fx_summarize_append: redo only the summary blocks that hold tokens at or after prev_len[b]."""
+    assert prev_len.dtype == torch.int32
+    c = layout.c_struct()
+    _check(lib().fx_summarize_append(ctypes.byref(c), _dptr(K), _dptr(summaries), _dptr(prev_len), max_new_tokens,
+                                     _stream(stream)), "fx_summarize_append")
+
+
 def sparse_decode(layout: Layout, q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, idx: torch.Tensor,
                   cnt: torch.Tensor, *, k_max: int, sink_tokens: int, window_tokens: int, out: torch.Tensor,
-                  workspace: torch.Tensor, stream=None) -> None:
-    """fx_sparse_decode: split-K sparse attention + merge into out (float32 [batch,Hq,d])."""
+                  workspace: torch.Tensor, stream=None, group_union: bool = False) -> None:
+    """fx_sparse_decode (or fx_sparse_decode_union): split-K sparse attention + merge into out
+    (float32 [batch,Hq,d])."""
     c = layout.c_struct()
+    fn = lib().fx_sparse_decode_union if group_union else lib().fx_sparse_decode
     _check(
-        lib().fx_sparse_decode(
+        fn(
             ctypes.byref(c), _dptr(q), _dptr(K), _dptr(V), _dptr(idx), _dptr(cnt), k_max, sink_tokens,
             window_tokens, _dptr(out), _dptr(workspace), workspace.numel() * workspace.element_size(),
             _stream(stream),

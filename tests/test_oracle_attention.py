@@ -213,3 +213,44 @@ def test_chunked_merge_survives_large_logit_spread():
     a = O.sparse_attention(L, q, K, V, idx, cnt, **kw)
     c = O.sparse_attention(L, q, K, V, idx, cnt, mode="chunked", chunk_tokens=32, **kw)
     assert np.abs(a - c).max() < 1e-12
+
+
+def test_group_union_token_set_and_special_cases():
+    """Union variant: the token set is the set-union of the group's selections (restated here); with one
+    head per group it is the head's own set; if one head of a group selects everything the whole group is
+    dense."""
+    wl, t = small_workload(seed=12)
+    L = oracle_layout(wl)
+    q, K, V = host_arrays(t)
+    S = O.summarize(L, K)
+    kw = dict(sink_tokens=wl.sink_tokens, window_tokens=wl.window_tokens)
+    bud = np.tile(np.array([0.1, 0.3, 0.0, 0.2, 1.0, 0.05], dtype=np.float32), (wl.batch, 1))
+    idx, cnt, _, _ = O.select(L, q, S, budget_frac=bud, k_max=L.max_blocks(), **kw)
+    G = wl.group
+    for b in range(wl.batch):
+        for h in range(wl.n_q_heads):
+            j = h // G
+            g = wl.gran[j]
+            N = wl.seq_len[b]
+            nb, n_sink, w0 = geometry(N, g, wl.sink_tokens, wl.window_tokens)
+            blocks = {i for i in range(nb) if i < n_sink or i >= w0}
+            for hh in range(j * G, (j + 1) * G):
+                blocks |= set(idx[b, hh, : cnt[b, hh]].tolist())
+            tokens, w = O.token_weights(L, q, K, V, idx, cnt, b=b, h=h, group_union=True, **kw)
+            assert tokens.tolist() == [tk for tk in range(N) if tk // g in blocks]
+            assert abs(w.sum() - 1) < 1e-12
+    uni = O.sparse_attention(L, q, K, V, idx, cnt, group_union=True, **kw)
+    dense = O.dense_attention(L, q, K, V)
+    assert np.abs(uni[:, 3:] - dense[:, 3:]).max() < 1e-12      # heads 3-5 share a group with a dense head
+    own = O.sparse_attention(L, q, K, V, idx, cnt, **kw)
+    assert np.abs(uni[:, :3] - own[:, :3]).max() > 1e-6          # heads 0-2 really see more tokens
+    # G = 1: union == own
+    wl1 = W.Workload(name="mha", n_q_heads=3, n_kv_heads=3, head_dim=64, seq_len=[400], gran=[16, 16, 32],
+                     sink_tokens=16, window_tokens=32, seed=1)
+    t1 = W.make_layer(wl1)
+    L1 = oracle_layout(wl1)
+    q1, K1, V1 = host_arrays(t1)
+    i1, c1, _, _ = O.select(L1, q1, O.summarize(L1, K1), budget_frac=0.2, sink_tokens=16, window_tokens=32, k_max=32)
+    a = O.sparse_attention(L1, q1, K1, V1, i1, c1, sink_tokens=16, window_tokens=32, group_union=True)
+    c = O.sparse_attention(L1, q1, K1, V1, i1, c1, sink_tokens=16, window_tokens=32)
+    assert np.array_equal(a, c)
