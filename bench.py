@@ -193,6 +193,20 @@ def measure(ls: LayerSet, steps: int, warmup: int, use_graph: bool) -> dict:
     }
 
 
+def profiled_traffic(workload: str, kernel: str = "attend_kernel"):
+    """HBM bytes per launch of the dominant kernel measured with rocprofv3 hardware counters (FETCH_SIZE and
+    WRITE_SIZE runs, summarised under profiles/); None if no profile of this workload is committed."""
+    path = os.path.join(ROOT, "profiles", "traffic.txt")
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) == 3 and f[0] == workload and f[1] == kernel:
+                return float(f[2])
+    except OSError:
+        pass
+    return None
+
+
 def stream_probe(n_bytes=4 << 30) -> dict:
     """Plain streaming read and plain copy of a buffer far larger than the caches: what this machine reaches
     with no arithmetic at all (context for the roofline fraction, and the known-size transfers that
@@ -312,6 +326,7 @@ def main():
     head["attend_frac_of_stream_read"] = head["attend_GBps"] / probe["read_GBps"]
     for r in others:
         r["attend_frac_of_stream_read"] = r["attend_GBps"] / probe["read_GBps"]
+        r["attend_traffic_bytes"] = profiled_traffic(r["workload"])
 
     base = None
     if not args.no_cpu_baseline:
@@ -344,7 +359,7 @@ def main():
         "roofline": {
             "bound": "hbm", "kernel": "attend_kernel (split-K sparse attention)",
             "achieved": head["attend_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-            "frac": head["attend_frac_of_hbm_peak"], "traffic": None,
+            "frac": head["attend_frac_of_hbm_peak"], "traffic": profiled_traffic(head["workload"]),
             "bytes_per_launch": head["decode_unique_bytes"], "us_per_launch": head["kernel_us"]["attend"],
         },
         "stream_probe": probe,
