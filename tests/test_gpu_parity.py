@@ -303,3 +303,33 @@ def test_biased_channels_with_heavy_cancellation():
           flush=True)
     assert (err <= gamma * mag[..., :nb][ok] / 8).all()
     assert differ == 0
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_shapes_sweep(seed):
+    """Random small problems: head_dim, group size, block sizes, ragged lengths, sink/window sizes and budgets
+    all drawn at random; every stage against the oracle."""
+    rng = np.random.default_rng(1000 + seed)
+    d = int(rng.choice([64, 128]))
+    G = int(rng.choice([1, 2, 3, 4, 5, 6, 7, 8]))
+    Hkv = int(rng.integers(1, 4))
+    B = int(rng.integers(1, 5))
+    gran = [int(g) for g in rng.choice([16, 32, 48, 64, 96, 128], size=Hkv)]
+    seq_len = [int(x) for x in rng.integers(1, 6000, size=B)]
+    sink = int(rng.choice([0, 16, 64, 100]))
+    window = int(rng.choice([0, 64, 256, 300]))
+    bud = rng.choice([0.0, 0.02, 0.1, 0.5, 1.0], size=(B, Hkv * G)).astype(np.float32)
+    wl = W.Workload(name=f"rand{seed}", n_q_heads=Hkv * G, n_kv_heads=Hkv, head_dim=d, seq_len=seq_len, gran=gran,
+                    sink_tokens=sink, window_tokens=window, budget_frac=bud, seed=seed,
+                    outlier_channels=int(rng.choice([0, 4])), q_mode=str(rng.choice(["normal", "near_key"])))
+    print(f"seed={seed} d={d} G={G} Hkv={Hkv} seq_len={seq_len} gran={gran} sink={sink} window={window}", flush=True)
+    t = W.make_layer(wl)
+    ref = run_oracle(wl, t)
+    gp = GpuProblem(wl, t, k_max=ref["k_max"])
+    gp.summarize()
+    assert np.array_equal(bf16_bits_to_f64(W.to_u16(gp.S))[: ref["S"].shape[0]], bf16_bits_to_f64(ref["S"]))
+    idx, cnt = gp.select()
+    exempt, differ = compare_selection(idx.cpu().numpy(), cnt.cpu().numpy(), ref["idx"], ref["cnt"], ref["gap"],
+                                       ref["kth"], ref["scores"], None)
+    out = gp.decode(ref["idx"], ref["cnt"]).cpu().numpy().astype(np.float64)
+    assert np.abs(out - ref["out"]).max() < TOL
