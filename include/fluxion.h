@@ -118,14 +118,16 @@ fx_status fx_select(const fx_layout* layout, const void* q, const void* summarie
                     const int32_t* budget_blocks, int32_t sink_tokens, int32_t window_tokens, int32_t k_max,
                     int32_t* idx, int32_t* cnt, void* workspace, size_t workspace_bytes, void* stream);
 
-/* Test aid: where fx_select leaves its intermediate per-block values inside the workspace after a call.
+/* Test aid: where fx_select leaves its intermediate values inside the workspace after a call.
  * For (b, h, block i) the approximate score is the float at byte offset
- *     *approx_offset + 4 * ((b * n_q_heads + h) * (*row_stride) + i)
- * and the magnitude sum that bounds its rounding error is at the same index from *mag_offset; only
- * candidate blocks are written.  `*gamma` is the factor of the bound |approx - exact| <= gamma * magnitude
- * that the selection relies on.  Returns INVALID_ARG/UNSUPPORTED for a bad layout. */
+ *     *approx_offset + 4 * ((b * n_q_heads + h) * (*row_stride) + i)            (candidate blocks only).
+ * The magnitude sums that bound its rounding error are kept as one maximum per 16 consecutive candidates:
+ * for candidate number c = i - n_sink it is the float at
+ *     *mag_offset + 4 * ((b * n_q_heads + h) * (*mag_stride) + c / 16).
+ * `*gamma` is the factor of the bound |approx - exact| <= gamma * magnitude that the selection relies on.
+ * Returns INVALID_ARG/UNSUPPORTED for a bad layout. */
 fx_status fx_select_workspace_view(const fx_layout* layout, size_t* approx_offset, size_t* mag_offset,
-                                   int64_t* row_stride, float* gamma);
+                                   int64_t* row_stride, int64_t* mag_stride, float* gamma);
 
 /* Bytes of scratch fx_sparse_decode needs (HOST computation; depends on the layout's host fields,
  * k_max, sink_tokens and window_tokens).  Returns 0 if the arguments are invalid. */

@@ -186,15 +186,16 @@ fx_status fx_select(const fx_layout* layout, const void* q, const void* summarie
 }
 
 fx_status fx_select_workspace_view(const fx_layout* layout, size_t* approx_offset, size_t* mag_offset,
-                                   int64_t* row_stride, float* gamma) {
+                                   int64_t* row_stride, int64_t* mag_stride, float* gamma) {
   fx::Params P;
   fx_status st = make_params(layout, 0, 0, 1, &P);
   if (st != FX_OK) return st;
-  if (!approx_offset || !mag_offset || !row_stride || !gamma) return FX_ERR_INVALID_ARG;
+  if (!approx_offset || !mag_offset || !row_stride || !mag_stride || !gamma) return FX_ERR_INVALID_ARG;
   const fx::SelectWorkspace W = fx::carve_select(P);
   *approx_offset = W.approx_off;
   *mag_offset = W.mag_off;
   *row_stride = P.nb_stride;
+  *mag_stride = W.mag_stride;
   *gamma = fx::select_error_gamma();
   return FX_OK;
 }

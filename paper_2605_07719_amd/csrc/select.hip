@@ -32,10 +32,6 @@ typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 // measured error of every candidate against this bound.
 constexpr float kGamma = 1.0f / 16384.0f;
 constexpr int kAmbCap = 256;  // band candidates re-scored in LDS; more => fallback
-#ifndef FX_SCORE_TILES
-#define FX_SCORE_TILES 2
-#endif
-constexpr int kScoreTilesPerWave = FX_SCORE_TILES;  // tiles of 16 candidates a wave walks through
 
 __device__ __forceinline__ uint64_t ordered_key64(double s) {
   uint64_t u = (uint64_t)__double_as_longlong(s);
@@ -58,20 +54,24 @@ __device__ __forceinline__ float key32_to_float(uint32_t k) {
 //   m = 0..7 : [q- | q+] of head m of the group      (-> s~, from B)
 //   m = 8..15: [|q-| | |q+|] of head m - 8            (-> a~, from |B|)
 // The summaries are loaded straight into the B layout (each lane 16 bytes of its own row).  Staging
-// them through LDS with fully coalesced loads was measured to be about twice slower.
+// them through LDS with fully coalesced loads was measured to be about twice slower, and loading with
+// four neighbouring lanes per row followed by a wave-wide permutation made no difference.
+// A wave walks `tiles_per_wave` consecutive tiles of 16 candidates, requesting the next tile's rows
+// before it multiplies the current one.  The magnitude sums are reduced to one maximum per tile and
+// head before they leave the kernel (the selection only needs their maximum per head).
 template <int kD>
 __global__ __launch_bounds__(256) void score_kernel(Params P, const uint16_t* __restrict__ q,
                                                     const uint16_t* __restrict__ S, float* __restrict__ approx,
-                                                    float* __restrict__ mag, const float* __restrict__ budget_frac,
-                                                    const int32_t* __restrict__ budget_blocks) {
+                                                    float* __restrict__ mag_tile, const float* __restrict__ budget_frac,
+                                                    const int32_t* __restrict__ budget_blocks, int tiles_per_wave,
+                                                    int mag_stride) {
   constexpr int kRow = 2 * kD;       // elements of one [mn | mx] row
   constexpr int kSlabs = kRow / 32;  // MFMA k-steps per row
-  constexpr int kTilesPerWave = kScoreTilesPerWave;
   const int b = blockIdx.z, j = blockIdx.y;
   const Geo geo = geometry(P, b, j);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n = lane & 15, r = lane >> 4;
-  const int tile_first = (blockIdx.x * 4 + wave) * kTilesPerWave;
+  const int tile_first = (blockIdx.x * 4 + wave) * tiles_per_wave;
   if (tile_first * 16 >= geo.n_cand) return;
   {
     // a group whose heads all have budget 0 (streaming heads, Sec. 3.2) needs no scores: its summaries
@@ -83,66 +83,72 @@ __global__ __launch_bounds__(256) void score_kernel(Params P, const uint16_t* __
     }
     if (!any) return;
   }
+  const int tile_end = min(tile_first + tiles_per_wave, (geo.n_cand + 15) >> 4);
 
-  // A operand, built once per wave from q
+  // A operand, built once per wave from q with bit operations on the packed bf16 pairs:
+  // q- keeps the negative elements, q+ the others; the magnitude rows drop the sign.
   uint4 a_op[kSlabs];
   {
     const int head = n & 7;
     const bool want_abs = n >= 8;
+    auto part = [&](uint32_t v, bool is_mx) -> uint32_t {
+      const uint32_t neg = ((v >> 15) & 0x00010001u) * 0xffffu;  // 0xffff in every half whose sign bit is set
+      const uint32_t kept = is_mx ? (v & ~neg) : (v & neg);
+      return want_abs ? (kept & 0x7fff7fffu) : kept;
+    };
 #pragma unroll
     for (int s = 0; s < kSlabs; ++s) {
       const int e = 32 * s + 8 * r;  // first row element of this lane's k-chunk
       const int c = e % kD;
       const bool is_mx = e >= kD;
-      float x[8];
-      if (head < P.group) {
-        const uint4 raw =
-            *reinterpret_cast<const uint4*>(q + ((int64_t)b * P.n_q_heads + j * P.group + head) * kD + c);
-        unpack8(raw, x);
-      } else {
-#pragma unroll
-        for (int t = 0; t < 8; ++t) x[t] = 0.f;
-      }
-#pragma unroll
-      for (int t = 0; t < 8; ++t) {
-        const float part = is_mx ? fmaxf(x[t], 0.f) : fminf(x[t], 0.f);
-        x[t] = want_abs ? fabsf(part) : part;
-      }
-      a_op[s] = pack8(x);
+      uint4 raw = make_uint4(0u, 0u, 0u, 0u);
+      if (head < P.group)
+        raw = *reinterpret_cast<const uint4*>(q + ((int64_t)b * P.n_q_heads + j * P.group + head) * kD + c);
+      a_op[s] = make_uint4(part(raw.x, is_mx), part(raw.y, is_mx), part(raw.z, is_mx), part(raw.w, is_mx));
     }
   }
 
   const uint16_t* rows = S + (P.sum_base[(int64_t)b * P.n_kv_heads + j] + geo.n_sink) * (int64_t)kRow + r * 8;
-  uint4 b_op[kTilesPerWave][kSlabs];
-#pragma unroll
-  for (int t = 0; t < kTilesPerWave; ++t) {
-    const int cand = min((tile_first + t) * 16 + n, geo.n_cand - 1);  // clamped: stays inside the candidates
+  uint4 cur[kSlabs], nxt[kSlabs];
+  auto fetch = [&](int tile, uint4* dst) {
+    const int cand = min(tile * 16 + n, geo.n_cand - 1);  // clamped: stays inside the candidates
     const uint16_t* p = rows + (int64_t)cand * kRow;
 #pragma unroll
-    for (int s = 0; s < kSlabs; ++s) b_op[t][s] = *reinterpret_cast<const uint4*>(p + 32 * s);
-  }
+    for (int s = 0; s < kSlabs; ++s) dst[s] = *reinterpret_cast<const uint4*>(p + 32 * s);
+  };
+  fetch(tile_first, nxt);
+  const int head_row = (4 * r) & 7;  // this lane's D rows are heads head_row .. head_row + 3
+  for (int tile = tile_first; tile < tile_end; ++tile) {
 #pragma unroll
-  for (int t = 0; t < kTilesPerWave; ++t) {
+    for (int s = 0; s < kSlabs; ++s) cur[s] = nxt[s];
+    if (tile + 1 < tile_end) fetch(tile + 1, nxt);
     f32x4_t d_s = {0.f, 0.f, 0.f, 0.f}, d_a = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int s = 0; s < kSlabs; ++s) {
-      const uint4 v = b_op[t][s];
+      const uint4 v = cur[s];
       const uint4 va = make_uint4(v.x & 0x7fff7fffu, v.y & 0x7fff7fffu, v.z & 0x7fff7fffu, v.w & 0x7fff7fffu);
       d_s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a_op[s]),
                                                     __builtin_bit_cast(bf16x8_t, v), d_s, 0, 0, 0);
       d_a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a_op[s]),
                                                     __builtin_bit_cast(bf16x8_t, va), d_a, 0, 0, 0);
     }
-    const int cand = (tile_first + t) * 16 + n;
-    if (cand < geo.n_cand) {
-      float* dst = r < 2 ? approx : mag;
+    const int cand = tile * 16 + n;
+    if (r < 2 && cand < geo.n_cand) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int head = (4 * r + i) & 7;
-        if (head < P.group)
-          dst[((int64_t)b * P.n_q_heads + j * P.group + head) * P.nb_stride + geo.n_sink + cand] =
-              r < 2 ? d_s[i] : d_a[i];
-      }
+      for (int i = 0; i < 4; ++i)
+        if (head_row + i < P.group)
+          approx[((int64_t)b * P.n_q_heads + j * P.group + head_row + i) * P.nb_stride + geo.n_sink + cand] = d_s[i];
+    }
+    // maximum magnitude over the tile's 16 candidates (clamped duplicates repeat a real candidate)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      float m = d_a[i];
+      m = fmaxf(m, dpp_f<kDppXor1>(m));
+      m = fmaxf(m, dpp_f<kDppXor2>(m));
+      m = fmaxf(m, dpp_f<kDppHalfMirror>(m));
+      m = fmaxf(m, dpp_f<kDppMirror>(m));
+      if (r >= 2 && n == 0 && head_row + i < P.group)
+        mag_tile[((int64_t)b * P.n_q_heads + j * P.group + head_row + i) * mag_stride + tile] = m;
     }
   }
 }
@@ -233,7 +239,8 @@ __global__ __launch_bounds__(256) void topk_kernel(Params P, const uint16_t* __r
                                                    const float* __restrict__ mag, uint64_t* __restrict__ keys64,
                                                    const float* __restrict__ budget_frac,
                                                    const int32_t* __restrict__ budget_blocks,
-                                                   int32_t* __restrict__ idx, int32_t* __restrict__ cnt) {
+                                                   int32_t* __restrict__ idx, int32_t* __restrict__ cnt,
+                                                   int mag_stride) {
   __shared__ int hist[256];
   __shared__ int scan_scratch[4];
   __shared__ int count_a[4];
@@ -258,7 +265,7 @@ __global__ __launch_bounds__(256) void topk_kernel(Params P, const uint16_t* __r
   int32_t* out = idx + slot * P.k_max;
   const int n = geo.n_cand;
   const float* ap = approx + slot * P.nb_stride + geo.n_sink;
-  const float* mg = mag + slot * P.nb_stride + geo.n_sink;
+  const float* mg = mag + slot * mag_stride;  // one maximum per tile of 16 candidates
 
   if (tid == 0) cnt[slot] = k;
   if (k == 0) {
@@ -272,7 +279,7 @@ __global__ __launch_bounds__(256) void topk_kernel(Params P, const uint16_t* __r
 
   // error bound of the approximate scores of this head
   float amax = 0.f;
-  for (int r = tid; r < n; r += 256) amax = fmaxf(amax, mg[r]);
+  for (int r = tid; r < (n + 15) >> 4; r += 256) amax = fmaxf(amax, mg[r]);
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) amax = fmaxf(amax, __shfl_xor(amax, off, kWave));
   if (lane == 0) s_wmax[wave] = amax;
@@ -403,7 +410,8 @@ __global__ __launch_bounds__(256) void topk_reg_kernel(Params P, const uint16_t*
                                                        const float* __restrict__ mag, uint64_t* __restrict__ keys64,
                                                        const float* __restrict__ budget_frac,
                                                        const int32_t* __restrict__ budget_blocks,
-                                                       int32_t* __restrict__ idx, int32_t* __restrict__ cnt) {
+                                                       int32_t* __restrict__ idx, int32_t* __restrict__ cnt,
+                                                       int mag_stride) {
   __shared__ int hist[256];
   __shared__ int scan_scratch[4];
   __shared__ int count_a[4];
@@ -430,7 +438,7 @@ __global__ __launch_bounds__(256) void topk_reg_kernel(Params P, const uint16_t*
   int32_t* out = idx + slot * P.k_max;
   const int n = geo.n_cand;
   const float* ap = approx + slot * P.nb_stride + geo.n_sink;
-  const float* mg = mag + slot * P.nb_stride + geo.n_sink;
+  const float* mg = mag + slot * mag_stride;  // one maximum per tile of 16 candidates
 
   if (tid == 0) cnt[slot] = k;
   if (k == 0) {
@@ -446,6 +454,7 @@ __global__ __launch_bounds__(256) void topk_reg_kernel(Params P, const uint16_t*
   const int r0 = tid * KPT;
   uint32_t key[KPT];
   float amax = 0.f;
+  for (int r = tid; r < (n + 15) >> 4; r += 256) amax = fmaxf(amax, mg[r]);
   uint32_t kmin = 0xffffffffu, kmax = 0u;
 #pragma unroll
   for (int i = 0; i < KPT; ++i) {
@@ -453,7 +462,6 @@ __global__ __launch_bounds__(256) void topk_reg_kernel(Params P, const uint16_t*
     key[i] = 0u;
     if (r < n) {
       key[i] = ordered_key32(ap[r]);
-      amax = fmaxf(amax, mg[r]);
       kmin = min(kmin, key[i]);
       kmax = max(kmax, key[i]);
     }
@@ -619,16 +627,21 @@ hipError_t launch_select(const Params& P, const void* q, const void* S, const fl
   float* approx = reinterpret_cast<float*>(ws + W.approx_off);
   float* mag = reinterpret_cast<float*>(ws + W.mag_off);
   uint64_t* keys = reinterpret_cast<uint64_t*>(ws + W.keys_off);
+  const int mag_stride = W.mag_stride;
   {
     ScopedSlot prof(kSlotScore, stream);
-    const int cand_per_wg = 4 * kScoreTilesPerWave * 16;  // 4 waves x tiles x 16 candidates
+    // tiles of 16 candidates per wave: enough workgroups to fill the chip first, then longer walks
+    const int64_t total_tiles = (int64_t)P.batch * P.n_kv_heads * mag_stride;
+    int tiles_per_wave = (int)(total_tiles / 4096);
+    tiles_per_wave = tiles_per_wave < 1 ? 1 : (tiles_per_wave > 8 ? 8 : tiles_per_wave);
+    const int cand_per_wg = 4 * tiles_per_wave * 16;
     dim3 sgrid((P.nb_stride + cand_per_wg - 1) / cand_per_wg, P.n_kv_heads, P.batch);
     if (P.head_dim == 128)
       hipLaunchKernelGGL(score_kernel<128>, sgrid, dim3(256), 0, stream, P, (const uint16_t*)q, (const uint16_t*)S,
-                         approx, mag, budget_frac, budget_blocks);
+                         approx, mag, budget_frac, budget_blocks, tiles_per_wave, mag_stride);
     else
       hipLaunchKernelGGL(score_kernel<64>, sgrid, dim3(256), 0, stream, P, (const uint16_t*)q, (const uint16_t*)S,
-                         approx, mag, budget_frac, budget_blocks);
+                         approx, mag, budget_frac, budget_blocks, tiles_per_wave, mag_stride);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -636,7 +649,7 @@ hipError_t launch_select(const Params& P, const void* q, const void* S, const fl
   const dim3 tgrid(P.n_q_heads, P.batch);
 #define FX_TOPK_ARGS                                                                                               \
   P, (const uint16_t*)q, (const uint16_t*)S, (const float*)approx, (const float*)mag, keys, budget_frac, budget_blocks, \
-      idx, cnt
+      idx, cnt, mag_stride
 #define FX_TOPK_REG(D, KPT) hipLaunchKernelGGL((topk_reg_kernel<D, KPT>), tgrid, dim3(256), 0, stream, FX_TOPK_ARGS)
   if (P.head_dim == 128) {
     if (P.nb_stride <= 1024) FX_TOPK_REG(128, 4);

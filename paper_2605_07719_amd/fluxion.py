@@ -194,12 +194,13 @@ def select_workspace_view(layout: Layout) -> dict:
     """fx_select_workspace_view: byte offsets of the approximate scores and their error magnitudes."""
     c = layout.c_struct()
     a, m = ctypes.c_size_t(), ctypes.c_size_t()
-    stride, gamma = ctypes.c_int64(), ctypes.c_float()
+    stride, mstride, gamma = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_float()
     fn = lib().fx_select_workspace_view
     fn.restype = ctypes.c_int
-    _check(fn(ctypes.byref(c), ctypes.byref(a), ctypes.byref(m), ctypes.byref(stride), ctypes.byref(gamma)),
-           "fx_select_workspace_view")
-    return {"approx_offset": a.value, "mag_offset": m.value, "row_stride": stride.value, "gamma": gamma.value}
+    _check(fn(ctypes.byref(c), ctypes.byref(a), ctypes.byref(m), ctypes.byref(stride), ctypes.byref(mstride),
+              ctypes.byref(gamma)), "fx_select_workspace_view")
+    return {"approx_offset": a.value, "mag_offset": m.value, "row_stride": stride.value,
+            "mag_stride": mstride.value, "gamma": gamma.value}
 
 
 def decode_workspace_bytes(layout: Layout, k_max: int, sink_tokens: int, window_tokens: int) -> int:
