@@ -118,13 +118,15 @@ fx_status fx_select(const fx_layout* layout, const void* q, const void* summarie
                     const int32_t* budget_blocks, int32_t sink_tokens, int32_t window_tokens, int32_t k_max,
                     int32_t* idx, int32_t* cnt, void* workspace, size_t workspace_bytes, void* stream);
 
-/* Test aid: where fx_select leaves its intermediate values inside the workspace after a call.
- * For (b, h, block i) the approximate score is the float at byte offset
- *     *approx_offset + 4 * ((b * n_q_heads + h) * (*row_stride) + i)            (candidate blocks only).
- * The magnitude sums that bound its rounding error are kept as one maximum per 16 consecutive candidates:
- * for candidate number c = i - n_sink it is the float at
+/* Test aid: where fx_select leaves its intermediate values inside the workspace after a call.  Candidates
+ * are numbered c = i - n_sink (block index minus the number of sink blocks) and handled in tiles of 16.
+ * With G = n_q_heads / n_kv_heads, j = h / G and r = h % G, the approximate score of candidate c for (b, h) is
+ * the float at byte offset
+ *     *approx_offset + 4 * ((((b * n_kv_heads + j) * (*mag_stride) + c / 16) * G + r) * 16 + c % 16)
+ * and the largest magnitude sum (the bound of the rounding error) over the tile of c is the float at
  *     *mag_offset + 4 * ((b * n_q_heads + h) * (*mag_stride) + c / 16).
- * `*gamma` is the factor of the bound |approx - exact| <= gamma * magnitude that the selection relies on.
+ * `*gamma` is the factor of the bound |approx - exact| <= gamma * magnitude that the selection relies on;
+ * `*row_stride` is the row length of the per-(b, h) block arrays (fallback keys).
  * Returns INVALID_ARG/UNSUPPORTED for a bad layout. */
 fx_status fx_select_workspace_view(const fx_layout* layout, size_t* approx_offset, size_t* mag_offset,
                                    int64_t* row_stride, int64_t* mag_stride, float* gamma);

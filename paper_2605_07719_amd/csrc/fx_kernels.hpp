@@ -12,9 +12,9 @@ namespace fx {
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
-// fx_select scratch: per (sequence, query head, block) the approximate score (fp32) and, for the exact
-// fallback path, one order-preserving 64-bit key; per (sequence, query head, tile of 16 candidates) the
-// largest magnitude sum (fp32).
+// fx_select scratch: the approximate scores (fp32, tile-major [sequence][KV head][tile][head of group][16]),
+// per (sequence, query head, tile of 16 candidates) the largest magnitude sum (fp32), and for the exact
+// fallback path one order-preserving 64-bit key per (sequence, query head, block).
 struct SelectWorkspace {
   size_t approx_off, mag_off, keys_off, total;
   int32_t mag_stride;  // tiles per (sequence, query head) row of the magnitude array
@@ -24,7 +24,7 @@ inline SelectWorkspace carve_select(const Params& P) {
   const size_t n = (size_t)P.batch * P.n_q_heads * P.nb_stride;
   W.mag_stride = (P.nb_stride + 15) / 16;
   size_t off = 0;
-  W.approx_off = off; off += align_up(n * sizeof(float));
+  W.approx_off = off; off += align_up((size_t)P.batch * P.n_q_heads * W.mag_stride * 16 * sizeof(float));
   W.mag_off = off;    off += align_up((size_t)P.batch * P.n_q_heads * W.mag_stride * sizeof(float));
   W.keys_off = off;   off += align_up(n * sizeof(uint64_t));
   W.total = off;

@@ -58,7 +58,9 @@ __device__ __forceinline__ float key32_to_float(uint32_t k) {
 // four neighbouring lanes per row followed by a wave-wide permutation made no difference.
 // A wave walks `tiles_per_wave` consecutive tiles of 16 candidates, requesting the next tile's rows
 // before it multiplies the current one.  The magnitude sums are reduced to one maximum per tile and
-// head before they leave the kernel (the selection only needs their maximum per head).
+// head before they leave the kernel (the selection only needs their maximum per head).  The scores
+// are stored tile-major, [sequence][KV head][tile][head of the group][16], so that a wave's stores for
+// a tile form one contiguous run of G * 64 bytes (scattered 64-byte pieces cost ~10% of the kernel).
 template <int kD>
 __global__ __launch_bounds__(256) void score_kernel(Params P, const uint16_t* __restrict__ q,
                                                     const uint16_t* __restrict__ S, float* __restrict__ approx,
@@ -137,7 +139,7 @@ __global__ __launch_bounds__(256) void score_kernel(Params P, const uint16_t* __
 #pragma unroll
       for (int i = 0; i < 4; ++i)
         if (head_row + i < P.group)
-          approx[((int64_t)b * P.n_q_heads + j * P.group + head_row + i) * P.nb_stride + geo.n_sink + cand] = d_s[i];
+          approx[((((int64_t)b * P.n_kv_heads + j) * mag_stride + tile) * P.group + head_row + i) * 16 + n] = d_s[i];
     }
     // maximum magnitude over the tile's 16 candidates (clamped duplicates repeat a real candidate)
 #pragma unroll
@@ -264,7 +266,10 @@ __global__ __launch_bounds__(256) void topk_kernel(Params P, const uint16_t* __r
   const int k = want > 0.0 ? (want < (double)limit ? (int)want : limit) : 0;  // NaN falls to 0
   int32_t* out = idx + slot * P.k_max;
   const int n = geo.n_cand;
-  const float* ap = approx + slot * P.nb_stride + geo.n_sink;
+  // approximate score of candidate r: tile-major [sequence][KV head][tile][head of the group][16]
+  const float* ap_base = approx + (((int64_t)b * P.n_kv_heads + j) * mag_stride * P.group + (h - j * P.group)) * 16;
+  const int tile_step = P.group * 16;
+  auto ap = [&](int r) { return ap_base[(int64_t)(r >> 4) * tile_step + (r & 15)]; };
   const float* mg = mag + slot * mag_stride;  // one maximum per tile of 16 candidates
 
   if (tid == 0) cnt[slot] = k;
@@ -289,7 +294,7 @@ __global__ __launch_bounds__(256) void topk_kernel(Params P, const uint16_t* __r
 
   uint32_t kth32;
   int krem32;
-  radix_select<uint32_t>([&](int r) { return ordered_key32(ap[r]); }, n, k, hist, scan_scratch, s_pair, kth32, krem32);
+  radix_select<uint32_t>([&](int r) { return ordered_key32(ap(r)); }, n, k, hist, scan_scratch, s_pair, kth32, krem32);
   const float T = key32_to_float(kth32);
   const float hi = T + eps2, lo = T - eps2;
 
@@ -298,7 +303,7 @@ __global__ __launch_bounds__(256) void topk_kernel(Params P, const uint16_t* __r
   {
     int c_sure = 0, c_amb = 0;
     for (int r = tid; r < n; r += 256) {
-      const float s = ap[r];
+      const float s = ap(r);
       c_sure += s > hi;
       c_amb += (s <= hi) && (s >= lo);
     }
@@ -356,7 +361,7 @@ __global__ __launch_bounds__(256) void topk_kernel(Params P, const uint16_t* __r
     int run = 0;
     for (int base = 0; base < n; base += 256) {
       const int r = base + tid;
-      const float s = r < n ? ap[r] : 0.f;
+      const float s = r < n ? ap(r) : 0.f;
       const bool amb = r < n && s <= hi && s >= lo;
       int tot;
       const int pos = run + block_excl_count(amb, count_a, tot);
@@ -385,7 +390,7 @@ __global__ __launch_bounds__(256) void topk_kernel(Params P, const uint16_t* __r
   int run_sel = 0, run_amb = 0;
   for (int base = 0; base < n; base += 256) {
     const int r = base + tid;
-    const float s = r < n ? ap[r] : 0.f;
+    const float s = r < n ? ap(r) : 0.f;
     const bool sure = r < n && s > hi;
     const bool amb = r < n && s <= hi && s >= lo;
     int tot_amb, tot_sel;
@@ -437,7 +442,9 @@ __global__ __launch_bounds__(256) void topk_reg_kernel(Params P, const uint16_t*
   const int k = want > 0.0 ? (want < (double)limit ? (int)want : limit) : 0;  // NaN falls to 0
   int32_t* out = idx + slot * P.k_max;
   const int n = geo.n_cand;
-  const float* ap = approx + slot * P.nb_stride + geo.n_sink;
+  // approximate scores: tile-major [sequence][KV head][tile][head of the group][16]
+  const float* ap_base = approx + (((int64_t)b * P.n_kv_heads + j) * mag_stride * P.group + (h - j * P.group)) * 16;
+  const int tile_step = P.group * 16;
   const float* mg = mag + slot * mag_stride;  // one maximum per tile of 16 candidates
 
   if (tid == 0) cnt[slot] = k;
@@ -457,13 +464,19 @@ __global__ __launch_bounds__(256) void topk_reg_kernel(Params P, const uint16_t*
   for (int r = tid; r < (n + 15) >> 4; r += 256) amax = fmaxf(amax, mg[r]);
   uint32_t kmin = 0xffffffffu, kmax = 0u;
 #pragma unroll
-  for (int i = 0; i < KPT; ++i) {
-    const int r = r0 + i;
-    key[i] = 0u;
-    if (r < n) {
-      key[i] = ordered_key32(ap[r]);
-      kmin = min(kmin, key[i]);
-      kmax = max(kmax, key[i]);
+  for (int i4 = 0; i4 < KPT; i4 += 4) {  // KPT and r0 are multiples of 4: four candidates never straddle a tile
+    const int r = r0 + i4;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (r < n) v = *reinterpret_cast<const float4*>(ap_base + (int64_t)(r >> 4) * tile_step + (r & 15));
+    const float f[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      key[i4 + u] = 0u;
+      if (r + u < n) {
+        key[i4 + u] = ordered_key32(f[u]);
+        kmin = min(kmin, key[i4 + u]);
+        kmax = max(kmax, key[i4 + u]);
+      }
     }
   }
 #pragma unroll

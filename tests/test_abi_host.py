@@ -62,7 +62,7 @@ def test_workspace_sizes_follow_host_fields():
     assert ws_bytes(HostLayout(max_seq_len=8192))[0] == 2 * a[0]            # per (b, h, block) scratch
     assert ws_bytes(HostLayout(batch=4))[0] == 2 * a[0]
     assert ws_bytes(HostLayout(), k_max=128)[1] >= a[1]
-    # select: fp32 score + u64 key per (batch, q head, block), fp32 magnitude per 16 blocks (256 B aligned)
+    # select: fp32 score (tiles of 16) + u64 key per (batch, q head, block), fp32 magnitude per 16 blocks
     assert a[0] == 2 * 8 * (4096 // 32) * 12 + 2 * 8 * 8 * 4
     assert ws_bytes(HostLayout(gran=(32, 24)))[0] == 0                       # invalid layout -> 0
 

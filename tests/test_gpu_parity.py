@@ -229,19 +229,23 @@ def _select_intermediates(gp):
 
     v = gp.F.select_workspace_view(gp.layout)
     wl = gp.wl
-    B, H = wl.batch, wl.n_q_heads
+    B, H, G, Hkv = wl.batch, wl.n_q_heads, wl.group, wl.n_kv_heads
     raw = gp.ws_select.cpu().numpy()
-    approx = raw[v["approx_offset"] : v["approx_offset"] + 4 * B * H * v["row_stride"]].view(np.float32)
-    approx = approx.reshape(B, H, v["row_stride"]).astype(np.float64)
-    tiles = raw[v["mag_offset"] : v["mag_offset"] + 4 * B * H * v["mag_stride"]].view(np.float32)
-    tiles = tiles.reshape(B, H, v["mag_stride"]).astype(np.float64)
+    n_tiles = v["mag_stride"]
+    a = raw[v["approx_offset"] : v["approx_offset"] + 4 * B * H * n_tiles * 16].view(np.float32)
+    a = a.reshape(B, Hkv, n_tiles, G, 16).astype(np.float64)
+    tiles = raw[v["mag_offset"] : v["mag_offset"] + 4 * B * H * n_tiles].view(np.float32)
+    tiles = tiles.reshape(B, H, n_tiles).astype(np.float64)
+    approx = np.full((B, H, v["row_stride"]), np.nan)
     mag = np.full_like(approx, np.nan)
     for b in range(B):
         for h in range(H):
-            g = wl.gran[h // wl.group]
+            g = wl.gran[h // G]
             nb, n_sink, w0 = geometry(wl.seq_len[b], g, wl.sink_tokens, wl.window_tokens)
             for i in range(n_sink, max(w0, n_sink)):
-                mag[b, h, i] = tiles[b, h, (i - n_sink) // 16]
+                c = i - n_sink
+                approx[b, h, i] = a[b, h // G, c // 16, h % G, c % 16]
+                mag[b, h, i] = tiles[b, h, c // 16]
     return approx, mag, v["gamma"]
 
 
