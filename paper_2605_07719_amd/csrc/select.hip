@@ -235,173 +235,219 @@ __device__ __forceinline__ void radix_select(Load load, int n, int k, int* hist,
   krem_out = krem;
 }
 
-template <int kD>
-__global__ __launch_bounds__(256) void topk_kernel(Params P, const uint16_t* __restrict__ q,
-                                                   const uint16_t* __restrict__ S, const float* __restrict__ approx,
-                                                   const float* __restrict__ mag, uint64_t* __restrict__ keys64,
-                                                   const float* __restrict__ budget_frac,
-                                                   const int32_t* __restrict__ budget_blocks,
-                                                   int32_t* __restrict__ idx, int32_t* __restrict__ cnt,
-                                                   int mag_stride) {
-  __shared__ int hist[256];
-  __shared__ int scan_scratch[4];
-  __shared__ int count_a[4];
-  __shared__ int count_b[4];
-  __shared__ int s_pair[2];
-  __shared__ float s_wmax[4];
-  __shared__ int amb_idx[kAmbCap];
-  __shared__ uint64_t amb_key[kAmbCap];
-  __shared__ unsigned char amb_chosen[kAmbCap];
+// LDS of one top-k workgroup.
+struct TopkShared {
+  int hist[256];
+  int scan[4];
+  int count_a[4];
+  int count_b[4];
+  int pair[2];
+  int total;
+  float wmax[4];
+  uint32_t kmin[4], kmax[4];
+  int amb_idx[kAmbCap];         // band candidates, ascending
+  uint64_t amb_key[kAmbCap];    // their exact keys
+  unsigned char amb_chosen[kAmbCap];
+};
 
-  const int b = blockIdx.y, h = blockIdx.x, j = h / P.group;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+// Everything the top-k of one (sequence, query head) needs.
+struct HeadTask {
+  int k, n, n_sink;           // blocks to keep, candidates, index of the first candidate block
+  int32_t* out;               // idx row of this head
+  const float* ap_base;       // approximate scores: candidate r at ap_base[(r / 16) * tile_step + r % 16]
+  int tile_step;
+  const float* mag;           // one magnitude maximum per tile of 16 candidates
+  const uint16_t* q_h;        // the head's query
+  const uint16_t* rows;       // [mn | mx] row of candidate 0
+  uint64_t* keys64;           // exact keys of the fallback path, candidate 0 first
+};
+
+struct TopkArgs {
+  const uint16_t* q;
+  const uint16_t* S;
+  const float* approx;
+  const float* mag;
+  uint64_t* keys64;
+  const float* budget_frac;
+  const int32_t* budget_blocks;
+  int32_t* idx;
+  int32_t* cnt;
+  int mag_stride;
+};
+
+// Fills the task of head blockIdx.x of sequence blockIdx.y, writes cnt, and finishes the two trivial
+// cases (nothing kept / everything kept) on the spot.  Returns false when the head is done.
+template <int kD>
+__device__ __forceinline__ bool begin_head(const Params& P, const TopkArgs& A, HeadTask& t) {
+  const int b = blockIdx.y, h = blockIdx.x, j = h / P.group, tid = threadIdx.x;
   const Geo geo = geometry(P, b, j);
   const int64_t slot = (int64_t)b * P.n_q_heads + h;
   double want;
-  if (budget_blocks)
-    want = (double)budget_blocks[slot];
+  if (A.budget_blocks)
+    want = (double)A.budget_blocks[slot];
   else
-    want = ceil((double)budget_frac[slot] * (double)geo.n_cand);
+    want = ceil((double)A.budget_frac[slot] * (double)geo.n_cand);
   const int limit = geo.n_cand < P.k_max ? geo.n_cand : P.k_max;
-  const int k = want > 0.0 ? (want < (double)limit ? (int)want : limit) : 0;  // NaN falls to 0
-  int32_t* out = idx + slot * P.k_max;
-  const int n = geo.n_cand;
-  // approximate score of candidate r: tile-major [sequence][KV head][tile][head of the group][16]
-  const float* ap_base = approx + (((int64_t)b * P.n_kv_heads + j) * mag_stride * P.group + (h - j * P.group)) * 16;
-  const int tile_step = P.group * 16;
-  auto ap = [&](int r) { return ap_base[(int64_t)(r >> 4) * tile_step + (r & 15)]; };
-  const float* mg = mag + slot * mag_stride;  // one maximum per tile of 16 candidates
-
-  if (tid == 0) cnt[slot] = k;
-  if (k == 0) {
-    for (int r = tid; r < P.k_max; r += 256) out[r] = -1;
-    return;
+  t.k = want > 0.0 ? (want < (double)limit ? (int)want : limit) : 0;  // NaN falls to 0
+  t.n = geo.n_cand;
+  t.n_sink = geo.n_sink;
+  t.out = A.idx + slot * P.k_max;
+  t.ap_base = A.approx + (((int64_t)b * P.n_kv_heads + j) * A.mag_stride * P.group + (h - j * P.group)) * 16;
+  t.tile_step = P.group * 16;
+  t.mag = A.mag + slot * A.mag_stride;
+  t.q_h = A.q + slot * kD;
+  t.rows = A.S + (P.sum_base[(int64_t)b * P.n_kv_heads + j] + geo.n_sink) * (int64_t)(2 * kD);
+  t.keys64 = A.keys64 + slot * P.nb_stride + geo.n_sink;
+  if (tid == 0) A.cnt[slot] = t.k;
+  if (t.k == 0 || t.k == t.n) {
+    for (int r = tid; r < P.k_max; r += 256) t.out[r] = r < t.k ? t.n_sink + r : -1;
+    return false;
   }
-  if (k == n) {
-    for (int r = tid; r < P.k_max; r += 256) out[r] = r < k ? geo.n_sink + r : -1;
-    return;
-  }
+  return true;
+}
 
-  // error bound of the approximate scores of this head
+// 2 * gamma * (largest magnitude sum of the head): half-width of the band around the k-th approximate score.
+__device__ __forceinline__ float band_half_width(const HeadTask& t, TopkShared& sh) {
+  const int tid = threadIdx.x;
   float amax = 0.f;
-  for (int r = tid; r < (n + 15) >> 4; r += 256) amax = fmaxf(amax, mg[r]);
+  for (int r = tid; r < (t.n + 15) >> 4; r += 256) amax = fmaxf(amax, t.mag[r]);
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) amax = fmaxf(amax, __shfl_xor(amax, off, kWave));
-  if (lane == 0) s_wmax[wave] = amax;
   __syncthreads();
-  amax = fmaxf(fmaxf(s_wmax[0], s_wmax[1]), fmaxf(s_wmax[2], s_wmax[3]));
-  const float eps2 = 2.0f * kGamma * amax * 1.001f + 1e-30f;
+  if ((tid & 63) == 0) sh.wmax[tid >> 6] = amax;
+  __syncthreads();
+  amax = fmaxf(fmaxf(sh.wmax[0], sh.wmax[1]), fmaxf(sh.wmax[2], sh.wmax[3]));
+  return 2.0f * kGamma * amax * 1.001f + 1e-30f;
+}
+
+// Exact path for a head whose band holds more candidates than LDS takes: exact fp64 scores for every
+// candidate, 64-bit radix select, ordered compaction (ties: lowest indices).
+template <int kD>
+__device__ __forceinline__ void exact_fallback(const Params& P, const HeadTask& t, TopkShared& sh) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  for (int r = wave; r < t.n; r += 4) {
+    const double s = exact_score_wave<kD>(t.q_h, t.rows + (int64_t)r * 2 * kD, lane);
+    if (lane == 0) t.keys64[r] = ordered_key64(s);
+  }
+  __threadfence_block();
+  __syncthreads();
+  uint64_t kth;
+  int krem;
+  radix_select<uint64_t>([&](int r) { return t.keys64[r]; }, t.n, t.k, sh.hist, sh.scan, sh.pair, kth, krem);
+  int run_sel = 0, run_eq = 0;
+  for (int base = 0; base < t.n; base += 256) {
+    const int r = base + tid;
+    const uint64_t key = r < t.n ? t.keys64[r] : 0ull;
+    const bool gt = r < t.n && key > kth;
+    const bool eq = r < t.n && key == kth;
+    int tot_eq, tot_sel;
+    const int eq_before = run_eq + block_excl_count(eq, sh.count_a, tot_eq);
+    const bool sel = gt || (eq && eq_before < krem);
+    const int pos = run_sel + block_excl_count(sel, sh.count_b, tot_sel);
+    if (sel && pos < P.k_max) t.out[pos] = t.n_sink + r;
+    run_eq += tot_eq;
+    run_sel += tot_sel;
+  }
+  for (int r = t.k + tid; r < P.k_max; r += 256) t.out[r] = -1;
+}
+
+// Band candidates sh.amb_idx[0 .. n_amb) (ascending) -> sh.amb_chosen: the `need` best by (exact score
+// descending, index ascending).
+template <int kD>
+__device__ __forceinline__ void resolve_band(const HeadTask& t, TopkShared& sh, int n_amb, int need) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  __syncthreads();  // amb_idx is complete
+  for (int a = wave; a < n_amb; a += 4) {
+    const double s = exact_score_wave<kD>(t.q_h, t.rows + (int64_t)sh.amb_idx[a] * 2 * kD, lane);
+    if (lane == 0) sh.amb_key[a] = ordered_key64(s);
+  }
+  __syncthreads();
+  if (tid < n_amb) {
+    const uint64_t mine = sh.amb_key[tid];
+    int rank = 0;
+    for (int a = 0; a < n_amb; ++a) {
+      const uint64_t other = sh.amb_key[a];
+      rank += (other > mine) || (other == mine && a < tid);
+    }
+    sh.amb_chosen[tid] = rank < need;
+  }
+  __syncthreads();
+}
+
+// Generic variant: any number of candidates, keys re-read from the workspace in every pass.
+template <int kD>
+__global__ __launch_bounds__(256) void topk_kernel(Params P, TopkArgs A) {
+  __shared__ TopkShared sh;
+  HeadTask t;
+  if (!begin_head<kD>(P, A, t)) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  auto ap = [&](int r) { return t.ap_base[(int64_t)(r >> 4) * t.tile_step + (r & 15)]; };
+  const float eps2 = band_half_width(t, sh);
 
   uint32_t kth32;
   int krem32;
-  radix_select<uint32_t>([&](int r) { return ordered_key32(ap(r)); }, n, k, hist, scan_scratch, s_pair, kth32, krem32);
+  radix_select<uint32_t>([&](int r) { return ordered_key32(ap(r)); }, t.n, t.k, sh.hist, sh.scan, sh.pair, kth32,
+                         krem32);
   const float T = key32_to_float(kth32);
   const float hi = T + eps2, lo = T - eps2;
 
   // classify: certainly kept (above the band) / ambiguous (inside the band)
-  int n_sure = 0, n_amb = 0;
-  {
-    int c_sure = 0, c_amb = 0;
-    for (int r = tid; r < n; r += 256) {
-      const float s = ap(r);
-      c_sure += s > hi;
-      c_amb += (s <= hi) && (s >= lo);
-    }
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      c_sure += __shfl_xor(c_sure, off, kWave);
-      c_amb += __shfl_xor(c_amb, off, kWave);
-    }
-    __syncthreads();
-    if (lane == 0) {
-      count_a[wave] = c_sure;
-      count_b[wave] = c_amb;
-    }
-    __syncthreads();
-    n_sure = count_a[0] + count_a[1] + count_a[2] + count_a[3];
-    n_amb = count_b[0] + count_b[1] + count_b[2] + count_b[3];
+  int c_sure = 0, c_amb = 0;
+  for (int r = tid; r < t.n; r += 256) {
+    const float s = ap(r);
+    c_sure += s > hi;
+    c_amb += (s <= hi) && (s >= lo);
   }
-  const int need = k - n_sure;  // 1 <= need <= n_amb by construction of the band around the k-th key
-  const uint16_t* q_h = q + slot * kD;
-  const uint16_t* rows = S + (P.sum_base[(int64_t)b * P.n_kv_heads + j] + geo.n_sink) * (int64_t)(2 * kD);
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    c_sure += __shfl_xor(c_sure, off, kWave);
+    c_amb += __shfl_xor(c_amb, off, kWave);
+  }
+  __syncthreads();
+  if (lane == 0) {
+    sh.count_a[wave] = c_sure;
+    sh.count_b[wave] = c_amb;
+  }
+  __syncthreads();
+  const int n_sure = sh.count_a[0] + sh.count_a[1] + sh.count_a[2] + sh.count_a[3];
+  const int n_amb = sh.count_b[0] + sh.count_b[1] + sh.count_b[2] + sh.count_b[3];
+  const int need = t.k - n_sure;  // 1 <= need <= n_amb by construction of the band around the k-th key
 
   if (need < n_amb && n_amb > kAmbCap) {
-    // Fallback: exact fp64 scores for every candidate, then an exact 64-bit radix select.
-    uint64_t* kh = keys64 + slot * P.nb_stride + geo.n_sink;
-    for (int r = wave; r < n; r += 4) {
-      const double s = exact_score_wave<kD>(q_h, rows + (int64_t)r * 2 * kD, lane);
-      if (lane == 0) kh[r] = ordered_key64(s);
-    }
-    __threadfence_block();
-    __syncthreads();
-    uint64_t kth64;
-    int krem64;
-    radix_select<uint64_t>([&](int r) { return kh[r]; }, n, k, hist, scan_scratch, s_pair, kth64, krem64);
-    int run_sel = 0, run_eq = 0;
-    for (int base = 0; base < n; base += 256) {
-      const int r = base + tid;
-      const uint64_t key = r < n ? kh[r] : 0ull;
-      const bool gt = r < n && key > kth64;
-      const bool eq = r < n && key == kth64;
-      int tot_eq, tot_sel;
-      const int eq_before = run_eq + block_excl_count(eq, count_a, tot_eq);
-      const bool sel = gt || (eq && eq_before < krem64);
-      const int pos = run_sel + block_excl_count(sel, count_b, tot_sel);
-      if (sel && pos < P.k_max) out[pos] = geo.n_sink + r;
-      run_eq += tot_eq;
-      run_sel += tot_sel;
-    }
-    for (int r = k + tid; r < P.k_max; r += 256) out[r] = -1;
+    exact_fallback<kD>(P, t, sh);
     return;
   }
-
   const bool resolve = need < n_amb;  // otherwise every band candidate is kept and no exact score is needed
   if (resolve) {
-    // band candidates, ascending by index, into LDS
     int run = 0;
-    for (int base = 0; base < n; base += 256) {
+    for (int base = 0; base < t.n; base += 256) {
       const int r = base + tid;
-      const float s = r < n ? ap(r) : 0.f;
-      const bool amb = r < n && s <= hi && s >= lo;
+      const float s = r < t.n ? ap(r) : 0.f;
+      const bool amb = r < t.n && s <= hi && s >= lo;
       int tot;
-      const int pos = run + block_excl_count(amb, count_a, tot);
-      if (amb) amb_idx[pos] = r;
+      const int pos = run + block_excl_count(amb, sh.count_a, tot);
+      if (amb) sh.amb_idx[pos] = r;
       run += tot;
     }
-    __syncthreads();
-    for (int a = wave; a < n_amb; a += 4) {
-      const double s = exact_score_wave<kD>(q_h, rows + (int64_t)amb_idx[a] * 2 * kD, lane);
-      if (lane == 0) amb_key[a] = ordered_key64(s);
-    }
-    __syncthreads();
-    if (tid < n_amb) {
-      const uint64_t mine = amb_key[tid];
-      int rank = 0;
-      for (int a = 0; a < n_amb; ++a) {
-        const uint64_t other = amb_key[a];
-        rank += (other > mine) || (other == mine && a < tid);
-      }
-      amb_chosen[tid] = rank < need;
-    }
-    __syncthreads();
+    resolve_band<kD>(t, sh, n_amb, need);
   }
 
   // ordered compaction of the kept candidates
   int run_sel = 0, run_amb = 0;
-  for (int base = 0; base < n; base += 256) {
+  for (int base = 0; base < t.n; base += 256) {
     const int r = base + tid;
-    const float s = r < n ? ap(r) : 0.f;
-    const bool sure = r < n && s > hi;
-    const bool amb = r < n && s <= hi && s >= lo;
+    const float s = r < t.n ? ap(r) : 0.f;
+    const bool sure = r < t.n && s > hi;
+    const bool amb = r < t.n && s <= hi && s >= lo;
     int tot_amb, tot_sel;
-    const int a = run_amb + block_excl_count(amb, count_a, tot_amb);
-    const bool sel = sure || (amb && (!resolve || amb_chosen[a]));
-    const int pos = run_sel + block_excl_count(sel, count_b, tot_sel);
-    if (sel && pos < P.k_max) out[pos] = geo.n_sink + r;
+    const int a = run_amb + block_excl_count(amb, sh.count_a, tot_amb);
+    const bool sel = sure || (amb && (!resolve || sh.amb_chosen[a]));
+    const int pos = run_sel + block_excl_count(sel, sh.count_b, tot_sel);
+    if (sel && pos < P.k_max) t.out[pos] = t.n_sink + r;
     run_amb += tot_amb;
     run_sel += tot_sel;
   }
-  for (int r = k + tid; r < P.k_max; r += 256) out[r] = -1;
+  for (int r = t.k + tid; r < P.k_max; r += 256) t.out[r] = -1;
 }
 
 // Register-resident variant for n_cand <= 256 * KPT: thread t owns the KPT consecutive candidates
@@ -409,70 +455,27 @@ __global__ __launch_bounds__(256) void topk_kernel(Params P, const uint16_t* __r
 // Keys are reduced to (key - smallest key) before the radix passes, which removes the sign/exponent
 // digits all candidates share: the select takes ceil(log2(span) / 8) passes, usually 3.
 template <int kD, int KPT>
-__global__ __launch_bounds__(256) void topk_reg_kernel(Params P, const uint16_t* __restrict__ q,
-                                                       const uint16_t* __restrict__ S,
-                                                       const float* __restrict__ approx,
-                                                       const float* __restrict__ mag, uint64_t* __restrict__ keys64,
-                                                       const float* __restrict__ budget_frac,
-                                                       const int32_t* __restrict__ budget_blocks,
-                                                       int32_t* __restrict__ idx, int32_t* __restrict__ cnt,
-                                                       int mag_stride) {
-  __shared__ int hist[256];
-  __shared__ int scan_scratch[4];
-  __shared__ int count_a[4];
-  __shared__ int count_b[4];
-  __shared__ int s_pair[2];
-  __shared__ int s_tot;
-  __shared__ float s_wmax[4];
-  __shared__ uint32_t s_kmin[4], s_kmax[4];
-  __shared__ int amb_idx[kAmbCap];
-  __shared__ uint64_t amb_key[kAmbCap];
-  __shared__ unsigned char amb_chosen[kAmbCap];
-
-  const int b = blockIdx.y, h = blockIdx.x, j = h / P.group;
+__global__ __launch_bounds__(256) void topk_reg_kernel(Params P, TopkArgs A) {
+  __shared__ TopkShared sh;
+  HeadTask t;
+  if (!begin_head<kD>(P, A, t)) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const Geo geo = geometry(P, b, j);
-  const int64_t slot = (int64_t)b * P.n_q_heads + h;
-  double want;
-  if (budget_blocks)
-    want = (double)budget_blocks[slot];
-  else
-    want = ceil((double)budget_frac[slot] * (double)geo.n_cand);
-  const int limit = geo.n_cand < P.k_max ? geo.n_cand : P.k_max;
-  const int k = want > 0.0 ? (want < (double)limit ? (int)want : limit) : 0;  // NaN falls to 0
-  int32_t* out = idx + slot * P.k_max;
-  const int n = geo.n_cand;
-  // approximate scores: tile-major [sequence][KV head][tile][head of the group][16]
-  const float* ap_base = approx + (((int64_t)b * P.n_kv_heads + j) * mag_stride * P.group + (h - j * P.group)) * 16;
-  const int tile_step = P.group * 16;
-  const float* mg = mag + slot * mag_stride;  // one maximum per tile of 16 candidates
+  const float eps2 = band_half_width(t, sh);
 
-  if (tid == 0) cnt[slot] = k;
-  if (k == 0) {
-    for (int r = tid; r < P.k_max; r += 256) out[r] = -1;
-    return;
-  }
-  if (k == n) {
-    for (int r = tid; r < P.k_max; r += 256) out[r] = r < k ? geo.n_sink + r : -1;
-    return;
-  }
-
-  // keys of this thread's candidates (0 = no candidate: below every real key), error bound, key range
+  // keys of this thread's candidates (0 = no candidate: below every real key) and the key range
   const int r0 = tid * KPT;
   uint32_t key[KPT];
-  float amax = 0.f;
-  for (int r = tid; r < (n + 15) >> 4; r += 256) amax = fmaxf(amax, mg[r]);
   uint32_t kmin = 0xffffffffu, kmax = 0u;
 #pragma unroll
   for (int i4 = 0; i4 < KPT; i4 += 4) {  // KPT and r0 are multiples of 4: four candidates never straddle a tile
     const int r = r0 + i4;
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (r < n) v = *reinterpret_cast<const float4*>(ap_base + (int64_t)(r >> 4) * tile_step + (r & 15));
+    if (r < t.n) v = *reinterpret_cast<const float4*>(t.ap_base + (int64_t)(r >> 4) * t.tile_step + (r & 15));
     const float f[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       key[i4 + u] = 0u;
-      if (r + u < n) {
+      if (r + u < t.n) {
         key[i4 + u] = ordered_key32(f[u]);
         kmin = min(kmin, key[i4 + u]);
         kmax = max(kmax, key[i4 + u]);
@@ -481,48 +484,44 @@ __global__ __launch_bounds__(256) void topk_reg_kernel(Params P, const uint16_t*
   }
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) {
-    amax = fmaxf(amax, __shfl_xor(amax, off, kWave));
     kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, off, kWave));
     kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, off, kWave));
   }
   if (lane == 0) {
-    s_wmax[wave] = amax;
-    s_kmin[wave] = kmin;
-    s_kmax[wave] = kmax;
+    sh.kmin[wave] = kmin;
+    sh.kmax[wave] = kmax;
   }
   __syncthreads();
-  amax = fmaxf(fmaxf(s_wmax[0], s_wmax[1]), fmaxf(s_wmax[2], s_wmax[3]));
-  kmin = min(min(s_kmin[0], s_kmin[1]), min(s_kmin[2], s_kmin[3]));
-  kmax = max(max(s_kmax[0], s_kmax[1]), max(s_kmax[2], s_kmax[3]));
-  const float eps2 = 2.0f * kGamma * amax * 1.001f + 1e-30f;
+  kmin = min(min(sh.kmin[0], sh.kmin[1]), min(sh.kmin[2], sh.kmin[3]));
+  kmax = max(max(sh.kmax[0], sh.kmax[1]), max(sh.kmax[2], sh.kmax[3]));
 
   // radix select of the k-th largest key on u = key - kmin, most significant digit first
   const uint32_t span = kmax - kmin;
   const int n_bits = span ? 32 - __clz((int)span) : 0;
   uint32_t prefix = 0;
-  int krem = k;
+  int krem = t.k;
   for (int pass = (n_bits + 7) / 8 - 1; pass >= 0; --pass) {
     const int shift = pass * 8;
     const uint32_t hi_mask = shift + 8 >= 32 ? 0u : (~0u << (shift + 8));
-    hist[tid] = 0;
+    sh.hist[tid] = 0;
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < KPT; ++i) {
       const uint32_t u = key[i] - kmin;
-      if (key[i] != 0u && (u & hi_mask) == prefix) atomicAdd(&hist[(u >> shift) & 255u], 1);
+      if (key[i] != 0u && (u & hi_mask) == prefix) atomicAdd(&sh.hist[(u >> shift) & 255u], 1);
     }
     __syncthreads();
     const int dg = 255 - tid;
-    const int c = hist[dg];
-    const int incl = block_incl_scan(c, scan_scratch);
+    const int c = sh.hist[dg];
+    const int incl = block_incl_scan(c, sh.scan);
     const int excl = incl - c;
     if (excl < krem && krem <= incl) {
-      s_pair[0] = dg;
-      s_pair[1] = krem - excl;
+      sh.pair[0] = dg;
+      sh.pair[1] = krem - excl;
     }
     __syncthreads();
-    prefix |= (uint32_t)s_pair[0] << shift;
-    krem = s_pair[1];
+    prefix |= (uint32_t)sh.pair[0] << shift;
+    krem = sh.pair[1];
     __syncthreads();
   }
   const float T = key32_to_float(kmin + prefix);
@@ -535,71 +534,28 @@ __global__ __launch_bounds__(256) void topk_reg_kernel(Params P, const uint16_t*
     c_sure += key[i] > hi_key;
     c_amb += key[i] >= lo_key && key[i] <= hi_key;
   }
-  const int sure_incl = block_incl_scan(c_sure, scan_scratch);
-  if (tid == 255) s_tot = sure_incl;
+  const int sure_incl = block_incl_scan(c_sure, sh.scan);
+  if (tid == 255) sh.total = sure_incl;
   __syncthreads();
-  const int n_sure = s_tot;
-  const int amb_incl = block_incl_scan(c_amb, scan_scratch);
-  if (tid == 255) s_tot = amb_incl;
+  const int n_sure = sh.total;
+  const int amb_incl = block_incl_scan(c_amb, sh.scan);
+  if (tid == 255) sh.total = amb_incl;
   __syncthreads();
-  const int n_amb = s_tot;
+  const int n_amb = sh.total;
   const int amb_base = amb_incl - c_amb;
-  const int need = k - n_sure;  // 1 <= need <= n_amb by construction of the band around the k-th key
-  const uint16_t* q_h = q + slot * kD;
-  const uint16_t* rows = S + (P.sum_base[(int64_t)b * P.n_kv_heads + j] + geo.n_sink) * (int64_t)(2 * kD);
+  const int need = t.k - n_sure;  // 1 <= need <= n_amb by construction of the band around the k-th key
 
   if (need < n_amb && n_amb > kAmbCap) {
-    // Fallback: exact fp64 scores for every candidate, then an exact 64-bit radix select.
-    uint64_t* kh = keys64 + slot * P.nb_stride + geo.n_sink;
-    for (int r = wave; r < n; r += 4) {
-      const double s = exact_score_wave<kD>(q_h, rows + (int64_t)r * 2 * kD, lane);
-      if (lane == 0) kh[r] = ordered_key64(s);
-    }
-    __threadfence_block();
-    __syncthreads();
-    uint64_t kth64;
-    int krem64;
-    radix_select<uint64_t>([&](int r) { return kh[r]; }, n, k, hist, scan_scratch, s_pair, kth64, krem64);
-    int run_sel = 0, run_eq = 0;
-    for (int base = 0; base < n; base += 256) {
-      const int r = base + tid;
-      const uint64_t key64 = r < n ? kh[r] : 0ull;
-      const bool gt = r < n && key64 > kth64;
-      const bool eq = r < n && key64 == kth64;
-      int tot_eq, tot_sel;
-      const int eq_before = run_eq + block_excl_count(eq, count_a, tot_eq);
-      const bool sel = gt || (eq && eq_before < krem64);
-      const int pos = run_sel + block_excl_count(sel, count_b, tot_sel);
-      if (sel && pos < P.k_max) out[pos] = geo.n_sink + r;
-      run_eq += tot_eq;
-      run_sel += tot_sel;
-    }
-    for (int r = k + tid; r < P.k_max; r += 256) out[r] = -1;
+    exact_fallback<kD>(P, t, sh);
     return;
   }
-
   const bool resolve = need < n_amb;  // otherwise every band candidate is kept and no exact score is needed
   if (resolve) {
     int a = amb_base;
 #pragma unroll
     for (int i = 0; i < KPT; ++i)
-      if (key[i] >= lo_key && key[i] <= hi_key) amb_idx[a++] = r0 + i;
-    __syncthreads();
-    for (int e = wave; e < n_amb; e += 4) {
-      const double s = exact_score_wave<kD>(q_h, rows + (int64_t)amb_idx[e] * 2 * kD, lane);
-      if (lane == 0) amb_key[e] = ordered_key64(s);
-    }
-    __syncthreads();
-    if (tid < n_amb) {
-      const uint64_t mine = amb_key[tid];
-      int rank = 0;
-      for (int e = 0; e < n_amb; ++e) {
-        const uint64_t other = amb_key[e];
-        rank += (other > mine) || (other == mine && e < tid);
-      }
-      amb_chosen[tid] = rank < need;
-    }
-    __syncthreads();
+      if (key[i] >= lo_key && key[i] <= hi_key) sh.amb_idx[a++] = r0 + i;
+    resolve_band<kD>(t, sh, n_amb, need);
   }
 
   // ordered compaction of the kept candidates
@@ -609,25 +565,23 @@ __global__ __launch_bounds__(256) void topk_reg_kernel(Params P, const uint16_t*
     int a = amb_base;
 #pragma unroll
     for (int i = 0; i < KPT; ++i) {
-      const bool sure = key[i] > hi_key;
-      const bool amb = key[i] >= lo_key && key[i] <= hi_key;
-      bool sel = sure;
-      if (amb) {
-        sel = !resolve || amb_chosen[a];
+      bool sel = key[i] > hi_key;
+      if (key[i] >= lo_key && key[i] <= hi_key) {
+        sel = !resolve || sh.amb_chosen[a];
         ++a;
       }
       sel_bits |= (uint32_t)sel << i;
       c_sel += sel;
     }
   }
-  int pos = block_incl_scan(c_sel, scan_scratch) - c_sel;
+  int pos = block_incl_scan(c_sel, sh.scan) - c_sel;
 #pragma unroll
   for (int i = 0; i < KPT; ++i)
     if ((sel_bits >> i) & 1u) {
-      if (pos < P.k_max) out[pos] = geo.n_sink + r0 + i;
+      if (pos < P.k_max) t.out[pos] = t.n_sink + r0 + i;
       ++pos;
     }
-  for (int r = k + tid; r < P.k_max; r += 256) out[r] = -1;
+  for (int r = t.k + tid; r < P.k_max; r += 256) t.out[r] = -1;
 }
 
 float select_error_gamma() { return kGamma; }
@@ -660,25 +614,23 @@ hipError_t launch_select(const Params& P, const void* q, const void* S, const fl
   if (e != hipSuccess) return e;
   ScopedSlot prof(kSlotTopk, stream);
   const dim3 tgrid(P.n_q_heads, P.batch);
-#define FX_TOPK_ARGS                                                                                               \
-  P, (const uint16_t*)q, (const uint16_t*)S, (const float*)approx, (const float*)mag, keys, budget_frac, budget_blocks, \
-      idx, cnt, mag_stride
-#define FX_TOPK_REG(D, KPT) hipLaunchKernelGGL((topk_reg_kernel<D, KPT>), tgrid, dim3(256), 0, stream, FX_TOPK_ARGS)
+  const TopkArgs A{(const uint16_t*)q, (const uint16_t*)S, approx, mag, keys, budget_frac, budget_blocks, idx, cnt,
+                   mag_stride};
+#define FX_TOPK_REG(D, KPT) hipLaunchKernelGGL((topk_reg_kernel<D, KPT>), tgrid, dim3(256), 0, stream, P, A)
   if (P.head_dim == 128) {
     if (P.nb_stride <= 1024) FX_TOPK_REG(128, 4);
     else if (P.nb_stride <= 2048) FX_TOPK_REG(128, 8);
     else if (P.nb_stride <= 4096) FX_TOPK_REG(128, 16);
     else if (P.nb_stride <= 8192) FX_TOPK_REG(128, 32);
-    else hipLaunchKernelGGL(topk_kernel<128>, tgrid, dim3(256), 0, stream, FX_TOPK_ARGS);
+    else hipLaunchKernelGGL(topk_kernel<128>, tgrid, dim3(256), 0, stream, P, A);
   } else {
     if (P.nb_stride <= 1024) FX_TOPK_REG(64, 4);
     else if (P.nb_stride <= 2048) FX_TOPK_REG(64, 8);
     else if (P.nb_stride <= 4096) FX_TOPK_REG(64, 16);
     else if (P.nb_stride <= 8192) FX_TOPK_REG(64, 32);
-    else hipLaunchKernelGGL(topk_kernel<64>, tgrid, dim3(256), 0, stream, FX_TOPK_ARGS);
+    else hipLaunchKernelGGL(topk_kernel<64>, tgrid, dim3(256), 0, stream, P, A);
   }
 #undef FX_TOPK_REG
-#undef FX_TOPK_ARGS
   return hipGetLastError();
 }
 
