@@ -34,13 +34,29 @@ __global__ __launch_bounds__(256) void plan_kernel(Params P, const int32_t* __re
   const int n_words = (geo.n_blocks + 3) >> 2;
   for (int w = tid; w < n_words; w += 256) mask_words[w] = 0u;
   __syncthreads();
-  for (int r = 0; r < P.group; ++r) {
-    const int64_t slot = (int64_t)b * P.n_q_heads + j * P.group + r;
-    int c = cnt[slot];
-    c = c < 0 ? 0 : (c > P.k_max ? P.k_max : c);
-    for (int e = tid; e < c; e += 256) {
-      const int i = idx[slot * P.k_max + e];
-      if (i >= 0 && i < geo.n_blocks) atomicOr(&mask_words[i >> 2], (1u << r) << ((i & 3) * 8));
+  // The heads' index lists are cut into pieces of 512 entries and the pieces are dealt to the 4 waves
+  // round-robin, so short lists of different heads are walked concurrently and a long list is shared by
+  // all waves; a lane keeps eight index loads in flight before the LDS atomics that consume them.
+  {
+    const int wave = tid >> 6, lane = tid & 63;
+    int piece_no = 0;
+    for (int r = 0; r < P.group; ++r) {
+      const int64_t slot = (int64_t)b * P.n_q_heads + j * P.group + r;
+      int c = cnt[slot];
+      c = c < 0 ? 0 : (c > P.k_max ? P.k_max : c);
+      const int32_t* list = idx + slot * P.k_max;
+      for (int base = 0; base < c; base += 512, ++piece_no) {
+        if ((piece_no & 3) != wave) continue;
+        int i[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int e = base + u * 64 + lane;
+          i[u] = e < c ? list[e] : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+          if (i[u] >= 0 && i[u] < geo.n_blocks) atomicOr(&mask_words[i[u] >> 2], (1u << r) << ((i[u] & 3) * 8));
+      }
     }
   }
   __syncthreads();
