@@ -236,6 +236,37 @@ def stream_probe(n_bytes=4 << 30) -> dict:
             "copy_GBps_read_plus_write": 2 * n_bytes / copy_ms / 1e6}
 
 
+def output_deviation(ls: LayerSet) -> dict:
+    """The paper's output-aware criterion (Eq. 2) used as a report: ||o_h(sparse) - o_h|| / max_h' ||o_h'|| of
+    the selected-block output against full attention (budget 1.0 through the same kernels), for each head
+    attending to its own selection and for the group-union variant.  Layer 0, untimed."""
+    import torch
+
+    F, wl = ls.F, ls.wl
+    q, K, V, S = ls.layers[0]
+    pl = ls.pl
+    k_all = int(pl.n_blocks.max())
+    kw = dict(sink_tokens=wl.sink_tokens, window_tokens=wl.window_tokens)
+    idx = torch.empty((wl.batch, wl.n_q_heads, k_all), dtype=torch.int32, device=q.device)
+    cnt = torch.empty((wl.batch, wl.n_q_heads), dtype=torch.int32, device=q.device)
+    ws = torch.empty(F.decode_workspace_bytes(ls.layout, k_all, wl.sink_tokens, wl.window_tokens), dtype=torch.uint8,
+                     device=q.device)
+    outs = {}
+    one = torch.ones((wl.batch, wl.n_q_heads), dtype=torch.float32, device=q.device)
+    for name, bf, bb, union in (("dense", one, None, False), ("own", ls.bf, ls.bb, False), ("union", ls.bf, ls.bb, True)):
+        out = torch.empty_like(ls.out)
+        F.select(ls.layout, q, S, budget_frac=bf, budget_blocks=bb, k_max=k_all, idx=idx, cnt=cnt, workspace=ls.ws_sel,
+                 **kw)
+        F.sparse_decode(ls.layout, q, K, V, idx, cnt, k_max=k_all, out=out, workspace=ws, group_union=union, **kw)
+        outs[name] = out.double()
+    scale = outs["dense"].norm(dim=-1).amax(dim=-1, keepdim=True)      # max over heads, per sequence
+    res = {}
+    for name in ("own", "union"):
+        dev = (outs[name] - outs["dense"]).norm(dim=-1) / scale
+        res[name] = {"mean": float(dev.mean()), "max": float(dev.max())}
+    return res
+
+
 def cpu_baseline(wl, seconds=12.0) -> dict:
     """The oracle, as it stands, on this machine's host cores: selection + sparse attention of one layer-step."""
     import torch
@@ -307,7 +338,11 @@ def main():
         head_wl = wl
     else:
         head_wl = W.llama_stack()
-        head = measure(LayerSet(head_wl, head_wl.n_layers), args.steps, args.warmup, use_graph)
+        head_ls = LayerSet(head_wl, head_wl.n_layers)
+        head = measure(head_ls, args.steps, args.warmup, use_graph)
+        head["eq2_output_deviation"] = output_deviation(head_ls)
+        del head_ls
+        torch.cuda.empty_cache()
     log("[bench] headline:", json.dumps(head))
 
     others = []
