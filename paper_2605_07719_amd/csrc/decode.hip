@@ -30,6 +30,15 @@ __global__ __launch_bounds__(256) void plan_kernel(Params P, const int32_t* __re
   __shared__ int scratch[4];
   const int b = blockIdx.y, j = blockIdx.x, tid = threadIdx.x;
   const int grp = b * P.n_kv_heads + j;
+  int counts[kMaxGroup];  // requested before the geometry so they arrive together with the sequence length
+#pragma unroll
+  for (int r = 0; r < kMaxGroup; ++r) {
+    counts[r] = 0;
+    if (r < P.group) {
+      const int c = cnt[(int64_t)b * P.n_q_heads + j * P.group + r];
+      counts[r] = c < 0 ? 0 : (c > P.k_max ? P.k_max : c);
+    }
+  }
   const Geo geo = geometry(P, b, j);
   const int n_words = (geo.n_blocks + 3) >> 2;
   for (int w = tid; w < n_words; w += 256) mask_words[w] = 0u;
@@ -40,10 +49,11 @@ __global__ __launch_bounds__(256) void plan_kernel(Params P, const int32_t* __re
   {
     const int wave = tid >> 6, lane = tid & 63;
     int piece_no = 0;
-    for (int r = 0; r < P.group; ++r) {
+#pragma unroll
+    for (int r = 0; r < kMaxGroup; ++r) {
+      if (r >= P.group) break;
       const int64_t slot = (int64_t)b * P.n_q_heads + j * P.group + r;
-      int c = cnt[slot];
-      c = c < 0 ? 0 : (c > P.k_max ? P.k_max : c);
+      const int c = counts[r];
       const int32_t* list = idx + slot * P.k_max;
       for (int base = 0; base < c; base += 512, ++piece_no) {
         if ((piece_no & 3) != wave) continue;
@@ -320,54 +330,54 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
   }
 }
 
-// One workgroup per (sequence, query head).  Pass 1 finds the global maximum over the group's items;
-// pass 2 spreads the items over 256 / (kD/4) slices of threads, each thread owning 4 channels, and adds
-// acc * 2^(m - M); the slices are then summed in a fixed order.
+// One workgroup per (sequence, query head).  The group's items are spread over 256 / (kD/4) slices of
+// threads, each thread owning 4 channels; a slice folds its items into a running (max, sum, accumulator)
+// in item order, and the slices are then fused in slice order (fixed order => reproducible results).
 template <int kD>
 __global__ __launch_bounds__(256) void merge_kernel(Params P, const int32_t* __restrict__ sched,
                                                     const float* __restrict__ acc_part,
                                                     const float* __restrict__ ml_part, float* __restrict__ out,
                                                     int items_cap) {
   constexpr int kLanesC = kD / 4;          // threads per item (4 channels each)
-  constexpr int kSlices = 256 / kLanesC;   // items in flight per pass-2 iteration
-  __shared__ float s_max[4];
+  constexpr int kSlices = 256 / kLanesC;   // items in flight per iteration
   __shared__ float s_o[kSlices][kD];
-  __shared__ float s_l[kSlices];
+  __shared__ float s_m[kSlices], s_l[kSlices];
   const int b = blockIdx.y, h = blockIdx.x, tid = threadIdx.x;
   const int G = P.group, j = h / G, r = h % G;
   const int grp = b * P.n_kv_heads + j;
   const int p0 = min(sched[grp], items_cap), p1 = min(sched[grp + 1], items_cap);
 
-  float M = kNegBig;
-  for (int it = p0 + tid; it < p1; it += 256) M = fmaxf(M, ml_part[((int64_t)it * G + r) * 2]);
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) M = fmaxf(M, __shfl_xor(M, off, kWave));
-  if ((tid & 63) == 0) s_max[tid >> 6] = M;
-  __syncthreads();
-  M = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
-
   const int slice = tid / kLanesC, cl = tid % kLanesC;
   float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
-  float L = 0.f;
+  float m_run = kNegBig, L = 0.f;
   // loads are unconditional (an item in which this head took no part contributes exact zeros), so
   // the compiler can keep several iterations in flight
 #pragma unroll 4
   for (int it = p0 + slice; it < p1; it += kSlices) {
     const float2 ml = *reinterpret_cast<const float2*>(ml_part + ((int64_t)it * G + r) * 2);
     const float4 a = *reinterpret_cast<const float4*>(acc_part + ((int64_t)it * G + r) * kD + cl * 4);
-    const float w = __builtin_amdgcn_exp2f(ml.x - M);
-    L += ml.y * w;
-    o.x += a.x * w; o.y += a.y * w; o.z += a.z * w; o.w += a.w * w;
+    const float m_new = fmaxf(m_run, ml.x);
+    const float keep = __builtin_amdgcn_exp2f(m_run - m_new), w = __builtin_amdgcn_exp2f(ml.x - m_new);
+    L = L * keep + ml.y * w;
+    o.x = o.x * keep + a.x * w; o.y = o.y * keep + a.y * w; o.z = o.z * keep + a.z * w; o.w = o.w * keep + a.w * w;
+    m_run = m_new;
   }
   *reinterpret_cast<float4*>(&s_o[slice][cl * 4]) = o;
-  if (cl == 0) s_l[slice] = L;
+  if (cl == 0) {
+    s_m[slice] = m_run;
+    s_l[slice] = L;
+  }
   __syncthreads();
   if (tid < kD) {
+    float M = s_m[0];
+#pragma unroll
+    for (int sl = 1; sl < kSlices; ++sl) M = fmaxf(M, s_m[sl]);
     float acc = 0.f, Lt = 0.f;
 #pragma unroll
     for (int sl = 0; sl < kSlices; ++sl) {
-      acc += s_o[sl][tid];
-      Lt += s_l[sl];
+      const float w = __builtin_amdgcn_exp2f(s_m[sl] - M);
+      acc += s_o[sl][tid] * w;
+      Lt += s_l[sl] * w;
     }
     out[((int64_t)b * P.n_q_heads + h) * kD + tid] = Lt > 0.f ? acc / Lt : 0.f;
   }

@@ -307,10 +307,9 @@ __device__ __forceinline__ bool begin_head(const Params& P, const TopkArgs& A, H
 }
 
 // 2 * gamma * (largest magnitude sum of the head): half-width of the band around the k-th approximate score.
-__device__ __forceinline__ float band_half_width(const HeadTask& t, TopkShared& sh) {
+// `amax` is this thread's partial maximum over the head's tile magnitudes.
+__device__ __forceinline__ float band_half_width(float amax, TopkShared& sh) {
   const int tid = threadIdx.x;
-  float amax = 0.f;
-  for (int r = tid; r < (t.n + 15) >> 4; r += 256) amax = fmaxf(amax, t.mag[r]);
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) amax = fmaxf(amax, __shfl_xor(amax, off, kWave));
   __syncthreads();
@@ -382,7 +381,9 @@ __global__ __launch_bounds__(256) void topk_kernel(Params P, TopkArgs A) {
   if (!begin_head<kD>(P, A, t)) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   auto ap = [&](int r) { return t.ap_base[(int64_t)(r >> 4) * t.tile_step + (r & 15)]; };
-  const float eps2 = band_half_width(t, sh);
+  float amax = 0.f;
+  for (int r = tid; r < (t.n + 15) >> 4; r += 256) amax = fmaxf(amax, t.mag[r]);
+  const float eps2 = band_half_width(amax, sh);
 
   uint32_t kth32;
   int krem32;
@@ -457,25 +458,46 @@ __global__ __launch_bounds__(256) void topk_kernel(Params P, TopkArgs A) {
 template <int kD, int KPT>
 __global__ __launch_bounds__(256) void topk_reg_kernel(Params P, TopkArgs A) {
   __shared__ TopkShared sh;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r0 = tid * KPT;
+  // The approximate scores and tile magnitudes of this thread are requested first: their addresses do not
+  // depend on the sequence length, so they travel together with the loads the geometry waits for instead
+  // of after them.  Slots past the last candidate hold stale data and are masked below.
+  float4 raw[KPT / 4];
+  float mag_raw[2];
+  {
+    const int h = blockIdx.x, j = h / P.group;
+    const float* ap_base =
+        A.approx + (((int64_t)blockIdx.y * P.n_kv_heads + j) * A.mag_stride * P.group + (h - j * P.group)) * 16;
+#pragma unroll
+    for (int i4 = 0; i4 < KPT; i4 += 4) {  // KPT and r0 are multiples of 4: four candidates never straddle a tile
+      const int r = r0 + i4;
+      raw[i4 / 4] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (r < A.mag_stride * 16)
+        raw[i4 / 4] = *reinterpret_cast<const float4*>(ap_base + (int64_t)(r >> 4) * (P.group * 16) + (r & 15));
+    }
+    const float* mg = A.mag + ((int64_t)blockIdx.y * P.n_q_heads + h) * A.mag_stride;
+#pragma unroll
+    for (int u = 0; u < 2; ++u) mag_raw[u] = tid + u * 256 < A.mag_stride ? mg[tid + u * 256] : 0.f;  // <= 512 tiles
+  }
   HeadTask t;
   if (!begin_head<kD>(P, A, t)) return;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const float eps2 = band_half_width(t, sh);
+  float amax = 0.f;
+#pragma unroll
+  for (int u = 0; u < 2; ++u)
+    if (tid + u * 256 < (t.n + 15) >> 4) amax = fmaxf(amax, mag_raw[u]);
+  const float eps2 = band_half_width(amax, sh);
 
   // keys of this thread's candidates (0 = no candidate: below every real key) and the key range
-  const int r0 = tid * KPT;
   uint32_t key[KPT];
   uint32_t kmin = 0xffffffffu, kmax = 0u;
 #pragma unroll
-  for (int i4 = 0; i4 < KPT; i4 += 4) {  // KPT and r0 are multiples of 4: four candidates never straddle a tile
-    const int r = r0 + i4;
-    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (r < t.n) v = *reinterpret_cast<const float4*>(t.ap_base + (int64_t)(r >> 4) * t.tile_step + (r & 15));
-    const float f[4] = {v.x, v.y, v.z, v.w};
+  for (int i4 = 0; i4 < KPT; i4 += 4) {
+    const float f[4] = {raw[i4 / 4].x, raw[i4 / 4].y, raw[i4 / 4].z, raw[i4 / 4].w};
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       key[i4 + u] = 0u;
-      if (r + u < t.n) {
+      if (r0 + i4 + u < t.n) {
         key[i4 + u] = ordered_key32(f[u]);
         kmin = min(kmin, key[i4 + u]);
         kmax = max(kmax, key[i4 + u]);
