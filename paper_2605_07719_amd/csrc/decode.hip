@@ -8,14 +8,17 @@
 //                  per-block head mask, add the sink and window blocks for every head, and compact
 //                  the non-empty blocks into an ascending "union list" of (block, head mask) entries.
 //                  A block that several heads of the group want is then read from HBM once.
-//   attend_kernel  persistent workgroups walk work items; an item is a chunk of one group's union
-//                  list.  Each wave takes 16-token slices of the chunk: coalesced 16-byte-per-lane
-//                  loads of K and V rows, fp32 dot products reduced inside the 8/16 lanes that share
-//                  a token, running (max, sum, accumulator) per head in registers.  Per item one
-//                  partial triple per head is written.  The chunk length adapts to the total amount
-//                  of selected work so that small steps still spread over the whole chip.
-//   merge_kernel   per (sequence, query head): fuse the partial triples of the group's items in
-//                  item order (fixed order => reproducible results).
+//   attend_kernel  the union lists of all groups, cut into 16-token slices, form one global slice
+//                  sequence; every workgroup of the launch takes an equal contiguous share of it (a
+//                  "unit"), so the work per workgroup is balanced whatever the budgets, block sizes
+//                  and sequence lengths are.  Where a unit crosses from one group into the next it
+//                  is cut into segments.  Within a segment each wave takes every fourth slice:
+//                  coalesced 16-byte-per-lane loads of K and V rows, fp32 dot products reduced inside
+//                  the 8/16 lanes that share a token, running (max, sum, accumulator) per head in
+//                  registers.  Per segment one partial triple per head is written, to slot
+//                  unit + group (strictly increasing along the slice sequence, hence unique).
+//   merge_kernel   per (sequence, query head): fuse the partial triples of the group's segments in
+//                  slot order (fixed order => reproducible results).
 // Logits are kept in the log2 domain (q is pre-multiplied by log2(e)/sqrt(D)) so the exponentials
 // are single v_exp_f32 instructions.
 #include "fx_device.hpp"
@@ -25,7 +28,8 @@ namespace fx {
 
 __global__ __launch_bounds__(256) void plan_kernel(Params P, const int32_t* __restrict__ idx,
                                                    const int32_t* __restrict__ cnt, uint32_t* __restrict__ uni,
-                                                   int32_t* __restrict__ ucount, int union_cap) {
+                                                   int32_t* __restrict__ ucount, int union_cap,
+                                                   int32_t* __restrict__ claim_counter) {
   extern __shared__ uint32_t mask_words[];  // one byte of head mask per block, 4 blocks per word
   __shared__ int scratch[4];
   const int b = blockIdx.y, j = blockIdx.x, tid = threadIdx.x;
@@ -93,6 +97,76 @@ __global__ __launch_bounds__(256) void plan_kernel(Params P, const int32_t* __re
     }
   }
   if (tid == 255) ucount[grp] = incl < union_cap ? incl : union_cap;
+  if (grp == 0 && tid == 0) *claim_counter = 0;  // the attention kernel that follows claims units from it
+}
+
+// Division of the global slice sequence into units (a slice is 16 tokens of a union list).
+//
+// Throughput regime (at least kMinShare slices per workgroup): the first `n_static` units, one per
+// workgroup of the launch and taken by workgroup number, are equal shares of the leading part of the
+// sequence; the rest is cut into small units that workgroups claim from a counter as they become free.
+// The claimed part evens out the differences in speed between workgroups (equal shares finish up to
+// +-12% apart: waves of an older workgroup are served first on a CU, and the XCDs do not get identical
+// bandwidth).  Units may span several groups; a unit is then processed in one segment per group.
+//
+// Latency regime (fewer slices): the step is cut into units of one workgroup's share, at least 4 slices
+// (one per wave), and every group is padded to a whole number of units (`align`), so that no unit spans
+// two groups and no workgroup pays two segment latencies.  Nothing is claimed.
+//
+// Unit boundaries depend only on the slice counts and the launch size, never on which workgroup takes a
+// unit, so the partial results and their merge order are reproducible.
+struct Split {
+  int unit_s;      // slices per static unit
+  int static_end;  // first slice of the claimed part
+  int unit_d;      // slices per claimed unit
+  int n_static;
+  int n_claimed;
+  int align;       // groups start at multiples of this many slices in the (padded) sequence
+  __device__ __forceinline__ int unit_of(int slice) const {
+    return slice < static_end ? slice / unit_s : n_static + (slice - static_end) / unit_d;
+  }
+  __device__ __forceinline__ int unit_begin(int u) const {
+    return u < n_static ? u * unit_s : static_end + (u - n_static) * unit_d;
+  }
+  __device__ __forceinline__ int unit_len(int u) const { return u < n_static ? unit_s : unit_d; }
+};
+#ifndef FX_CLAIMED_PCT
+#define FX_CLAIMED_PCT 25   // share of the sequence that is claimed
+#endif
+#ifndef FX_MIN_SHARE
+#define FX_MIN_SHARE 64     // slices per workgroup from which the throughput regime applies
+#endif
+#ifndef FX_CLAIMED_UNIT
+#define FX_CLAIMED_UNIT 20  // slices per claimed unit (5 per wave); measured optimum between 12 and 28
+#endif
+__device__ __forceinline__ Split make_split(int total_slices, int n_wg) {
+  Split sp;
+  const int share = (total_slices + n_wg - 1) / n_wg;  // slices per workgroup if all were static
+  if (share < FX_MIN_SHARE) {
+    sp.unit_s = share < 4 ? 4 : ((share + 3) & ~3);
+    sp.align = sp.unit_s;
+    sp.unit_d = 4;
+    sp.n_claimed = 0;
+    sp.n_static = 0;    // both set by finish_split() once the padded total is known
+    sp.static_end = 0;
+    return sp;
+  }
+  sp.align = 1;
+  sp.n_static = n_wg;
+  sp.unit_s = ((int)((int64_t)share * (100 - FX_CLAIMED_PCT) / 100) + 3) & ~3;
+  sp.static_end = min(total_slices, sp.unit_s * n_wg);
+  const int rest = total_slices - sp.static_end;
+  // larger claimed units only where a workgroup would otherwise take more than kClaimedPerWg of them
+  const int d = ((rest + kClaimedPerWg * n_wg - 1) / (kClaimedPerWg * n_wg) + 3) & ~3;
+  sp.unit_d = d < FX_CLAIMED_UNIT ? FX_CLAIMED_UNIT : d;
+  sp.n_claimed = (rest + sp.unit_d - 1) / sp.unit_d;
+  return sp;
+}
+__device__ __forceinline__ void finish_split(Split& sp, int padded_total) {
+  if (sp.align > 1) {
+    sp.static_end = padded_total;
+    sp.n_static = padded_total / sp.unit_s;  // padded_total is a multiple of unit_s
+  }
 }
 
 template <int kD, int kG>
@@ -101,84 +175,92 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
                                                      const uint32_t* __restrict__ uni,
                                                      const int32_t* __restrict__ ucount, int union_cap,
                                                      int32_t* __restrict__ sched, float* __restrict__ acc_part,
-                                                     float* __restrict__ ml_part, int items_cap) {
+                                                     float* __restrict__ ml_part, int slots_cap) {
   constexpr int kLanes = kD / 8;        // lanes that share one token row
   constexpr int kTPL = 64 / kLanes;     // token rows per wave-wide load
   constexpr int kLoads = 16 / kTPL;     // loads per 16-token slice
   // register budget: prefetching pays only where it does not cost a resident wave (measured)
   constexpr bool kPrefetch = kD == 128 ? (kG == 6 || kG == 7) : (kG >= 7);
-  extern __shared__ int s_prefix[];     // [n_groups + 1] exclusive prefix of items per group
+  extern __shared__ int s_prefix[];     // [n_groups + 1] exclusive prefix of slices per group
   __shared__ float s_red[4][kG][kD + 2];
   __shared__ int s_scan[4];
-  __shared__ unsigned long long s_total;
-  __shared__ uint32_t s_ent[kMaxChunkEntries];
+  __shared__ uint32_t s_ent[kEntriesPerPiece];
+  __shared__ int s_claim;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int chunk = lane % kLanes, tslot = lane / kLanes;
   const int n_groups = P.batch * P.n_kv_heads;
 
-  // ---- split sizing, computed identically by every workgroup -------------------------------------
-  if (tid == 0) s_total = 0ull;
-  __syncthreads();
-  {
-    unsigned long long local = 0;
-    for (int g = tid; g < n_groups; g += 256) local += (unsigned long long)ucount[g] * P.gran[g % P.n_kv_heads];
-    if (local) atomicAdd(&s_total, local);
-  }
-  __syncthreads();
-  const unsigned long long total_tokens = s_total;
-  int shift = 0;
-  while (shift < kMaxChunkShift && total_tokens > (unsigned long long)kTargetItems * (kMinChunkTokens << shift)) ++shift;
-  const int chunk_tokens = kMinChunkTokens << shift;
+  // ---- the global slice sequence and its division, computed identically by every workgroup --------
+  Split split;
   {
     const int per = (n_groups + 255) / 256;
     const int g_lo = min(tid * per, n_groups), g_hi = min(g_lo + per, n_groups);
+    auto slices_of = [&](int g) { return ucount[g] * ((int)P.gran[g % P.n_kv_heads] >> 4); };
     int local = 0;
-    for (int g = g_lo; g < g_hi; ++g) {
-      const int cb = max(1, chunk_tokens / (int)P.gran[g % P.n_kv_heads]);
-      local += (ucount[g] + cb - 1) / cb;
+    for (int g = g_lo; g < g_hi; ++g) local += slices_of(g);
+    int incl = block_incl_scan(local, s_scan);
+    split = make_split(s_scan[0] + s_scan[1] + s_scan[2] + s_scan[3], (int)gridDim.x);
+    const int al = split.align;
+    if (al > 1) {  // second pass over the padded counts
+      local = 0;
+      for (int g = g_lo; g < g_hi; ++g) local += (slices_of(g) + al - 1) / al * al;
+      incl = block_incl_scan(local, s_scan);
     }
-    const int incl = block_incl_scan(local, s_scan);
     int run = incl - local;
     for (int g = g_lo; g < g_hi; ++g) {
       s_prefix[g] = run;
-      const int cb = max(1, chunk_tokens / (int)P.gran[g % P.n_kv_heads]);
-      run += (ucount[g] + cb - 1) / cb;
+      run += (slices_of(g) + al - 1) / al * al;
     }
-    if (tid == 255) s_prefix[n_groups] = incl;  // the last thread's inclusive sum is the item total
+    if (tid == 255) s_prefix[n_groups] = incl;  // the last thread's inclusive sum is the (padded) total
   }
   __syncthreads();
-  const int n_items = min(s_prefix[n_groups], items_cap);
+  const int total_slices = s_prefix[n_groups];
+  finish_split(split, total_slices);
   if (blockIdx.x == 0) {
     for (int g = tid; g <= n_groups; g += 256) sched[g] = s_prefix[g];
-    if (tid == 0) sched[n_groups + 1] = chunk_tokens;
+    if (tid == 0) {
+      sched[n_groups + 1] = split.unit_s;
+      sched[n_groups + 2] = split.static_end;
+      sched[n_groups + 3] = split.unit_d;
+      sched[n_groups + 4] = split.n_static;
+    }
   }
-
+  int32_t* claim_counter = sched + n_groups + 5;  // zeroed by plan_kernel
   const float q_scale = 1.4426950408889634f * rsqrtf((float)kD);
 
-  for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
-    // group of this item: the last g with s_prefix[g] <= item
+  int claimed = 0;
+  int unit = blockIdx.x;
+  for (;;) {
+  int s0 = 0, s1 = 0;
+  if (unit < split.n_static + split.n_claimed) {
+    s0 = split.unit_begin(unit);
+    s1 = min(s0 + split.unit_len(unit), unit < split.n_static ? split.static_end : total_slices);
+  }
+  const bool had_work = s0 < s1;
+  int grp = 0;  // group of slice s0: the last g with s_prefix[g] <= s0 (groups without slices are skipped)
+  if (s0 < s1) {
     int lo = 0, hi = n_groups - 1;
     while (lo < hi) {
       const int mid = (lo + hi + 1) >> 1;
-      if (s_prefix[mid] <= item) lo = mid; else hi = mid - 1;
+      if (s_prefix[mid] <= s0) lo = mid; else hi = mid - 1;
     }
-    const int grp = lo, b = grp / P.n_kv_heads, j = grp % P.n_kv_heads;
+    grp = lo;
+  }
+
+  while (s0 < s1) {
+    // ---- one segment: slices [s0, seg_end) of the sequence, all inside group `grp` ------------------
+    const int seg_end = min(s1, s_prefix[grp + 1]);
+    const int b = grp / P.n_kv_heads, j = grp % P.n_kv_heads;
     const Geo geo = geometry(P, b, j);
-    const int cb = max(1, chunk_tokens / geo.g);
-    const int n_union = ucount[grp];
-    const int e0 = (item - s_prefix[grp]) * cb;
-    const int e1 = min(e0 + cb, n_union);
     const int spb = geo.g >> 4;  // 16-token slices per block
-    const int n_slices = (e1 - e0) * spb;
+    // slices relative to the group's list (the end of a padded group is clipped to the list's length)
+    const int l0 = s0 - s_prefix[grp], l1 = min(seg_end - s_prefix[grp], ucount[grp] * spb);
+    const int e_lo = l0 / spb, e_hi = (l1 - 1) / spb;                  // union entries touched (inclusive)
     const uint32_t* entries = uni + (int64_t)grp * union_cap;
     const int64_t head_base = P.seq_base[b] + (int64_t)j * P.kv_head_stride + chunk * 8;
     const uint16_t* Kb = K + head_base;
     const uint16_t* Vb = V + head_base;
-
-    // the item's union entries go to LDS once, so the per-slice address chain starts from LDS
-    if (tid < e1 - e0) s_ent[tid] = entries[e0 + tid];
-    __syncthreads();
 
     // q stays packed (2 bf16 per register); the 1/sqrt(D) and log2(e) factors are applied to the dot product
     uint4 qp[kG];
@@ -198,10 +280,19 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
     uint4 kraw[kLoads], vraw[kLoads], knext[kLoads], vnext[kLoads];
     uint32_t mask_next = 0;
     int t0_next = 0;
+
+    // the segment's union entries pass through LDS in pieces, so the per-slice address chain starts from LDS
+    for (int pe = e_lo; pe <= e_hi; pe += kEntriesPerPiece) {
+    __syncthreads();  // the previous piece's readers are done
+    if (pe + tid <= e_hi) s_ent[tid] = entries[pe + tid];
+    __syncthreads();
+    const int p_lo = max(l0, pe * spb), p_hi = min(l1, (pe + kEntriesPerPiece) * spb);
+
     auto issue = [&](int sl, uint4* kr, uint4* vr, uint32_t& mask_out, int& t0_out) {
-      const uint32_t ent = __builtin_amdgcn_readfirstlane(s_ent[sl / spb]);
+      const int e = sl / spb;
+      const uint32_t ent = __builtin_amdgcn_readfirstlane(s_ent[e - pe]);
       mask_out = ent & 255u;
-      t0_out = (int)(ent >> 8) * geo.g + (sl % spb) * 16 + tslot;
+      t0_out = (int)(ent >> 8) * geo.g + (sl - e * spb) * 16 + tslot;
 #pragma unroll
       for (int i = 0; i < kLoads; ++i) {
         const int64_t row = (int64_t)min(t0_out + i * kTPL, geo.n_tokens - 1) * P.token_stride;
@@ -209,9 +300,9 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
         vr[i] = *reinterpret_cast<const uint4*>(Vb + row);
       }
     };
-    if (kPrefetch && wave < n_slices) issue(wave, knext, vnext, mask_next, t0_next);
+    if (kPrefetch && p_lo + wave < p_hi) issue(p_lo + wave, knext, vnext, mask_next, t0_next);
 
-    for (int sl = wave; sl < n_slices; sl += 4) {
+    for (int sl = p_lo + wave; sl < p_hi; sl += 4) {
       if (kPrefetch) {
 #pragma unroll
         for (int i = 0; i < kLoads; ++i) {
@@ -223,7 +314,7 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
       }
       const uint32_t mask = mask_next;
       const int t0 = t0_next;
-      if (kPrefetch && sl + 4 < n_slices) issue(sl + 4, knext, vnext, mask_next, t0_next);
+      if (kPrefetch && sl + 4 < p_hi) issue(sl + 4, knext, vnext, mask_next, t0_next);
 
       // logits (log2 domain) of the slice's tokens for every head that wants this block
       float sp[kG][kLoads];
@@ -280,8 +371,13 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
         }
       }
     }
+    }  // pieces
 
-    // ---- fuse the token slots of the wave, then the 4 waves, then write the item's partial --------
+    // the claim of the next unit is requested before the last segment's reduction, which hides its latency
+    if (seg_end == s1 && tid == 0 && split.n_claimed > 0) claimed = atomicAdd(claim_counter, 1);
+
+    // ---- fuse the token slots of the wave, then the 4 waves, then write the segment's partial -----
+    const int slot = min(unit + grp, slots_cap - 1);  // the clamp never binds (slots_cap >= units + groups)
 #pragma unroll
     for (int r = 0; r < kG; ++r) {
       float M = m_run[r];
@@ -320,66 +416,96 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
         o += s_red[w][r][c] * sc;
         L += s_red[w][r][kD + 1] * sc;
       }
-      acc_part[((int64_t)item * kG + r) * kD + c] = o;
+      acc_part[((int64_t)slot * kG + r) * kD + c] = o;
       if (c == 0) {
-        ml_part[((int64_t)item * kG + r) * 2] = M;
-        ml_part[((int64_t)item * kG + r) * 2 + 1] = L;
+        ml_part[((int64_t)slot * kG + r) * 2] = M;
+        ml_part[((int64_t)slot * kG + r) * 2 + 1] = L;
       }
     }
     __syncthreads();
+    s0 = seg_end;
+    do ++grp; while (grp < n_groups && s_prefix[grp + 1] <= s0);  // next group that has slices
+  }
+
+  // ---- next unit: claimed from the counter (every workgroup ends with a claim beyond the last unit) ----
+  if (unit < split.n_static && unit + (int)gridDim.x < split.n_static) {  // latency regime: units beyond one per workgroup
+    unit += gridDim.x;
+    continue;
+  }
+  if (split.n_claimed == 0) break;
+  if (tid == 0) s_claim = had_work ? claimed : atomicAdd(claim_counter, 1);
+  __syncthreads();
+  const int u = s_claim;
+  __syncthreads();
+  if (u >= split.n_claimed) break;
+  unit = split.n_static + u;
   }
 }
 
-// One workgroup per (sequence, query head).  The group's items are spread over 256 / (kD/4) slices of
-// threads, each thread owning 4 channels; a slice folds its items into a running (max, sum, accumulator)
-// in item order, and the slices are then fused in slice order (fixed order => reproducible results).
+// One workgroup per (sequence, query head, 32 output channels).  The group's partials (slots unit + group
+// of the units that overlap the group's part of the slice sequence) are spread over 32 rows of 8 threads,
+// each thread owning 4 channels; a row folds its partials into a running (max, sum, accumulator) in slot
+// order, and the rows are then fused in row order (fixed order => reproducible results).  A group with a
+// long union list (a dense head) has thousands of partials: hence 32 of them in flight per step.
+constexpr int kMergeCols = 32;
 template <int kD>
 __global__ __launch_bounds__(256) void merge_kernel(Params P, const int32_t* __restrict__ sched,
                                                     const float* __restrict__ acc_part,
                                                     const float* __restrict__ ml_part, float* __restrict__ out,
-                                                    int items_cap) {
-  constexpr int kLanesC = kD / 4;          // threads per item (4 channels each)
-  constexpr int kSlices = 256 / kLanesC;   // items in flight per iteration
-  __shared__ float s_o[kSlices][kD];
-  __shared__ float s_m[kSlices], s_l[kSlices];
-  const int b = blockIdx.y, h = blockIdx.x, tid = threadIdx.x;
+                                                    int slots_cap) {
+  constexpr int kLanesC = kMergeCols / 4;  // threads per partial (4 channels each)
+  constexpr int kRows = 256 / kLanesC;     // partials in flight per iteration
+  __shared__ float s_o[kRows][kMergeCols + 1];
+  __shared__ float s_m[kRows], s_l[kRows];
+  const int b = blockIdx.y, h = blockIdx.x, c0 = blockIdx.z * kMergeCols, tid = threadIdx.x;
   const int G = P.group, j = h / G, r = h % G;
   const int grp = b * P.n_kv_heads + j;
-  const int p0 = min(sched[grp], items_cap), p1 = min(sched[grp + 1], items_cap);
+  const int first = sched[grp], last = sched[grp + 1];
+  int p0 = 0, p1 = 0;
+  if (last > first) {
+    const int32_t* sp_raw = sched + P.batch * P.n_kv_heads + 1;
+    Split split;
+    split.unit_s = sp_raw[0];
+    split.static_end = sp_raw[1];
+    split.unit_d = sp_raw[2];
+    split.n_static = sp_raw[3];
+    p0 = min(split.unit_of(first) + grp, slots_cap);
+    p1 = min(split.unit_of(last - 1) + grp + 1, slots_cap);
+  }
 
-  const int slice = tid / kLanesC, cl = tid % kLanesC;
+  const int row = tid / kLanesC, cl = tid % kLanesC;
   float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
   float m_run = kNegBig, L = 0.f;
-  // loads are unconditional (an item in which this head took no part contributes exact zeros), so
+  // loads are unconditional (a segment in which this head took no part contributes exact zeros), so
   // the compiler can keep several iterations in flight
 #pragma unroll 4
-  for (int it = p0 + slice; it < p1; it += kSlices) {
+  for (int it = p0 + row; it < p1; it += kRows) {
     const float2 ml = *reinterpret_cast<const float2*>(ml_part + ((int64_t)it * G + r) * 2);
-    const float4 a = *reinterpret_cast<const float4*>(acc_part + ((int64_t)it * G + r) * kD + cl * 4);
+    const float4 a = *reinterpret_cast<const float4*>(acc_part + ((int64_t)it * G + r) * kD + c0 + cl * 4);
     const float m_new = fmaxf(m_run, ml.x);
     const float keep = __builtin_amdgcn_exp2f(m_run - m_new), w = __builtin_amdgcn_exp2f(ml.x - m_new);
     L = L * keep + ml.y * w;
     o.x = o.x * keep + a.x * w; o.y = o.y * keep + a.y * w; o.z = o.z * keep + a.z * w; o.w = o.w * keep + a.w * w;
     m_run = m_new;
   }
-  *reinterpret_cast<float4*>(&s_o[slice][cl * 4]) = o;
+  s_o[row][cl * 4 + 0] = o.x; s_o[row][cl * 4 + 1] = o.y; s_o[row][cl * 4 + 2] = o.z; s_o[row][cl * 4 + 3] = o.w;
   if (cl == 0) {
-    s_m[slice] = m_run;
-    s_l[slice] = L;
+    s_m[row] = m_run;
+    s_l[row] = L;
   }
   __syncthreads();
-  if (tid < kD) {
+  if (tid < kMergeCols) {
     float M = s_m[0];
 #pragma unroll
-    for (int sl = 1; sl < kSlices; ++sl) M = fmaxf(M, s_m[sl]);
+    for (int i = 1; i < kRows; ++i) M = fmaxf(M, s_m[i]);
     float acc = 0.f, Lt = 0.f;
 #pragma unroll
-    for (int sl = 0; sl < kSlices; ++sl) {
-      const float w = __builtin_amdgcn_exp2f(s_m[sl] - M);
-      acc += s_o[sl][tid] * w;
-      Lt += s_l[sl] * w;
+    for (int i = 0; i < kRows; ++i) {
+      const float w = __builtin_amdgcn_exp2f(s_m[i] - M);
+      acc += s_o[i][tid] * w;
+      Lt += s_l[i] * w;
     }
-    out[((int64_t)b * P.n_q_heads + h) * kD + tid] = Lt > 0.f ? acc / Lt : 0.f;
+    out[((int64_t)b * P.n_q_heads + h) * kD + c0 + tid] = Lt > 0.f ? acc / Lt : 0.f;
   }
 }
 
@@ -395,10 +521,10 @@ static hipError_t launch_attend(const Params& P, const void* q, const void* K, c
     wg_per_cu = n > 8 ? 8 : n;
   }
   int grid = n_cu * wg_per_cu;
-  if (grid > W.items_cap) grid = W.items_cap;
+  if (grid > kMaxUnits) grid = kMaxUnits;
   hipLaunchKernelGGL((attend_kernel<kD, kG>), dim3(grid), dim3(256), lds, stream, P, (const uint16_t*)q,
                      (const uint16_t*)K, (const uint16_t*)V, uni, ucount, W.union_cap, sched, acc_part, ml_part,
-                     W.items_cap);
+                     W.slots_cap);
   return hipGetLastError();
 }
 
@@ -430,7 +556,7 @@ hipError_t launch_decode(const Params& P, const void* q, const void* K, const vo
   {
     ScopedSlot prof(kSlotPlan, stream);
     hipLaunchKernelGGL(plan_kernel, dim3(P.n_kv_heads, P.batch), dim3(256), plan_lds, stream, P, idx, cnt, uni,
-                       ucount, W.union_cap);
+                       ucount, W.union_cap, sched + P.batch * P.n_kv_heads + 5);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -443,11 +569,11 @@ hipError_t launch_decode(const Params& P, const void* q, const void* K, const vo
   if (e != hipSuccess) return e;
   ScopedSlot prof(kSlotMerge, stream);
   if (P.head_dim == 128)
-    hipLaunchKernelGGL(merge_kernel<128>, dim3(P.n_q_heads, P.batch), dim3(256), 0, stream, P, (const int32_t*)sched,
-                       (const float*)acc_part, (const float*)ml_part, out, W.items_cap);
+    hipLaunchKernelGGL(merge_kernel<128>, dim3(P.n_q_heads, P.batch, 128 / kMergeCols), dim3(256), 0, stream, P, (const int32_t*)sched,
+                       (const float*)acc_part, (const float*)ml_part, out, W.slots_cap);
   else
-    hipLaunchKernelGGL(merge_kernel<64>, dim3(P.n_q_heads, P.batch), dim3(256), 0, stream, P, (const int32_t*)sched,
-                       (const float*)acc_part, (const float*)ml_part, out, W.items_cap);
+    hipLaunchKernelGGL(merge_kernel<64>, dim3(P.n_q_heads, P.batch, 64 / kMergeCols), dim3(256), 0, stream, P, (const int32_t*)sched,
+                       (const float*)acc_part, (const float*)ml_part, out, W.slots_cap);
   return hipGetLastError();
 }
 

@@ -31,54 +31,48 @@ inline SelectWorkspace carve_select(const Params& P) {
   return W;
 }
 
-// Split sizing of the decode stage.  A work item is one chunk of one group's union list; the chunk
-// length in tokens is 64 << s with the smallest s in [0, 4] that keeps the item count near kTargetItems.
-#ifndef FX_MAX_CHUNK_SHIFT
-#define FX_MAX_CHUNK_SHIFT 4
+// Work split of the decode stage.  The union lists of all groups, cut into 16-token slices, form one
+// sequence that is divided into units: one static unit per workgroup of the launch (at most kMaxUnits)
+// followed by up to kClaimedPerWg smaller units per workgroup that are claimed from a counter.  A unit
+// that spans several groups writes one partial result per group it touches, to slot unit + group.
+constexpr int kMaxUnits = 2048;
+#ifndef FX_CLAIMED_PER_WG
+#define FX_CLAIMED_PER_WG 8
 #endif
-#ifndef FX_TARGET_ITEMS
-#define FX_TARGET_ITEMS 4096
-#endif
-constexpr int kMinChunkTokens = 64;
-constexpr int kMaxChunkShift = FX_MAX_CHUNK_SHIFT;
-constexpr int kTargetItems = FX_TARGET_ITEMS;
+constexpr int kClaimedPerWg = FX_CLAIMED_PER_WG;
 constexpr int kMaxGroups = 4096;
-constexpr int kMaxChunkEntries = (kMinChunkTokens << kMaxChunkShift) / 16;  // smallest block is 16 tokens
+constexpr int kEntriesPerPiece = 256;  // union entries staged in LDS at a time
 
 // fx_sparse_decode scratch.
 struct DecodeWorkspace {
   int32_t union_cap;  // entries per group in the union list
-  int32_t items_cap;  // upper bound on work items
+  int32_t slots_cap;  // partial-result slots: units + groups
   size_t union_off;   // uint32 [n_groups][union_cap]   (block << 8) | head mask, ascending by block
   size_t ucount_off;  // int32  [n_groups]              entries per group
-  size_t sched_off;   // int32  [n_groups + 2]          exclusive item prefix, then total, then chunk tokens
-  size_t acc_off;     // float  [items_cap][group][d]   un-normalised partial outputs
-  size_t ml_off;      // float  [items_cap][group][2]   partial running maximum (log2 domain) and sum
+  size_t sched_off;   // int32  [n_groups + 8]          exclusive slice prefix, total, the split (4 values), claim counter
+  size_t acc_off;     // float  [slots_cap][group][d]   un-normalised partial outputs
+  size_t ml_off;      // float  [slots_cap][group][2]   partial running maximum (log2 domain) and sum
   size_t total;
 };
 inline DecodeWorkspace carve_decode(const Params& P) {
   DecodeWorkspace W;
   const int n_groups = P.batch * P.n_kv_heads;
-  int64_t ucap = 0, tokens_cap_per_seq = 0;
+  int64_t ucap = 0;
   for (int j = 0; j < P.n_kv_heads; ++j) {
     const int64_t g = P.gran[j];
     const int64_t nb = (P.max_seq_len + g - 1) / g;
     const int64_t always = (P.sink_tokens + g - 1) / g + (P.window_tokens + g - 1) / g + 1;
     const int64_t u = nb < always + (int64_t)P.group * P.k_max ? nb : always + (int64_t)P.group * P.k_max;
     if (u > ucap) ucap = u;
-    tokens_cap_per_seq += u * g;
   }
   if (ucap < 1) ucap = 1;
-  const int64_t tokens_cap = tokens_cap_per_seq * P.batch;
-  int64_t items = (tokens_cap + (kMinChunkTokens << kMaxChunkShift) - 1) / (kMinChunkTokens << kMaxChunkShift);
-  if (items < kTargetItems) items = kTargetItems;
-  items += n_groups;
+  const int64_t items = (int64_t)kMaxUnits * (1 + kClaimedPerWg) + 2 * n_groups + 8;
   W.union_cap = (int32_t)ucap;
-  W.items_cap = (int32_t)items;
+  W.slots_cap = (int32_t)items;
   size_t off = 0;
   W.union_off = off;  off += align_up((size_t)n_groups * ucap * sizeof(uint32_t));
   W.ucount_off = off; off += align_up((size_t)n_groups * sizeof(int32_t));
-  W.sched_off = off;  off += align_up((size_t)(n_groups + 2) * sizeof(int32_t));
+  W.sched_off = off;  off += align_up((size_t)(n_groups + 8) * sizeof(int32_t));
   W.acc_off = off;    off += align_up((size_t)items * P.group * P.head_dim * sizeof(float));
   W.ml_off = off;     off += align_up((size_t)items * P.group * 2 * sizeof(float));
   W.total = off;
