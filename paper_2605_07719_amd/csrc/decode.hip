@@ -179,13 +179,20 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
   constexpr int kLanes = kD / 8;        // lanes that share one token row
   constexpr int kTPL = 64 / kLanes;     // token rows per wave-wide load
   constexpr int kLoads = 16 / kTPL;     // loads per 16-token slice
-  // register budget: prefetching pays only where it does not cost a resident wave (measured)
-  constexpr bool kPrefetch = kD == 128 ? (kG == 6 || kG == 7) : (kG >= 7);
+  // Register budget.  Up to 5 heads per group every head's logits are computed first, then the softmax
+  // updates, then the accumulation (most independent work in flight; 3-5 resident waves per SIMD).  From 6
+  // heads on that order needs > 200 registers (2 resident waves), so a slice is processed one head at a
+  // time (only one head's probabilities live) and q is re-read from LDS per head: 142-160 registers,
+  // 3 resident waves (measured +4% at 7 heads per group; at 4 heads the LDS reads cost 3%).
+  constexpr bool kHeadMajor = kG >= 6;
+  // (Requesting the next slice before the current one is consumed costs 32 more registers and never paid
+  // for the resident wave it takes away: the loads in flight come from the resident waves.)
   extern __shared__ int s_prefix[];     // [n_groups + 1] exclusive prefix of slices per group
   __shared__ float s_red[4][kG][kD + 2];
   __shared__ int s_scan[4];
   __shared__ uint32_t s_ent[kEntriesPerPiece];
   __shared__ int s_claim;
+  __shared__ uint4 s_q[kHeadMajor ? kG : 1][kD / 8];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int chunk = lane % kLanes, tslot = lane / kLanes;
@@ -263,23 +270,22 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
     const uint16_t* Vb = V + head_base;
 
     // q stays packed (2 bf16 per register); the 1/sqrt(D) and log2(e) factors are applied to the dot product
-    uint4 qp[kG];
+    uint4 qp[kHeadMajor ? 1 : kG];
+    if constexpr (kHeadMajor) {  // visible to all waves after the barrier that precedes the first piece
+      if (tid < kG * kLanes)
+        s_q[tid / kLanes][tid % kLanes] = *reinterpret_cast<const uint4*>(
+            q + ((int64_t)b * P.n_q_heads + j * kG + tid / kLanes) * kD + (tid % kLanes) * 8);
+    }
     float acc[kG][8], m_run[kG], l_run[kG];
 #pragma unroll
     for (int r = 0; r < kG; ++r) {
-      qp[r] = *reinterpret_cast<const uint4*>(q + ((int64_t)b * P.n_q_heads + j * kG + r) * kD + chunk * 8);
+      if constexpr (!kHeadMajor)
+        qp[r] = *reinterpret_cast<const uint4*>(q + ((int64_t)b * P.n_q_heads + j * kG + r) * kD + chunk * 8);
 #pragma unroll
       for (int c = 0; c < 8; ++c) acc[r][c] = 0.f;
       m_run[r] = kNegBig;
       l_run[r] = 0.f;
     }
-
-    // With kPrefetch the K/V rows of the wave's next slice are requested before the current slice is
-    // consumed (one slice, 8 KiB at d = 128, always in flight per wave) at the price of 32 registers;
-    // without it the kernel relies on more resident waves per SIMD.
-    uint4 kraw[kLoads], vraw[kLoads], knext[kLoads], vnext[kLoads];
-    uint32_t mask_next = 0;
-    int t0_next = 0;
 
     // the segment's union entries pass through LDS in pieces, so the per-slice address chain starts from LDS
     for (int pe = e_lo; pe <= e_hi; pe += kEntriesPerPiece) {
@@ -288,85 +294,117 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
     __syncthreads();
     const int p_lo = max(l0, pe * spb), p_hi = min(l1, (pe + kEntriesPerPiece) * spb);
 
-    auto issue = [&](int sl, uint4* kr, uint4* vr, uint32_t& mask_out, int& t0_out) {
+    for (int sl = p_lo + wave; sl < p_hi; sl += 4) {
+      // the slice's 16 K rows and 16 V rows: kLoads wave-wide loads each, 16 bytes per lane
       const int e = sl / spb;
       const uint32_t ent = __builtin_amdgcn_readfirstlane(s_ent[e - pe]);
-      mask_out = ent & 255u;
-      t0_out = (int)(ent >> 8) * geo.g + (sl - e * spb) * 16 + tslot;
+      const uint32_t mask = ent & 255u;
+      const int t0 = (int)(ent >> 8) * geo.g + (sl - e * spb) * 16 + tslot;
+      uint4 kraw[kLoads], vraw[kLoads];
 #pragma unroll
       for (int i = 0; i < kLoads; ++i) {
-        const int64_t row = (int64_t)min(t0_out + i * kTPL, geo.n_tokens - 1) * P.token_stride;
-        kr[i] = *reinterpret_cast<const uint4*>(Kb + row);
-        vr[i] = *reinterpret_cast<const uint4*>(Vb + row);
+        const int64_t row = (int64_t)min(t0 + i * kTPL, geo.n_tokens - 1) * P.token_stride;
+        kraw[i] = *reinterpret_cast<const uint4*>(Kb + row);
+        vraw[i] = *reinterpret_cast<const uint4*>(Vb + row);
       }
-    };
-    if (kPrefetch && p_lo + wave < p_hi) issue(p_lo + wave, knext, vnext, mask_next, t0_next);
 
-    for (int sl = p_lo + wave; sl < p_hi; sl += 4) {
-      if (kPrefetch) {
+      if constexpr (kHeadMajor) {
 #pragma unroll
-        for (int i = 0; i < kLoads; ++i) {
-          kraw[i] = knext[i];
-          vraw[i] = vnext[i];
+        for (int r = 0; r < kG; ++r) {
+          if (mask & (1u << r)) {
+            __asm__ volatile("" ::: "memory");  // keeps the LDS read of q inside the loop instead of in registers
+            const uint4 qv = s_q[r][chunk];
+            float sp[kLoads];
+#pragma unroll
+            for (int i = 0; i < kLoads; ++i) {
+              const bool valid = t0 + i * kTPL < geo.n_tokens;
+              float dot = dot2_bf16(qv.x, kraw[i].x, 0.f);
+              dot = dot2_bf16(qv.y, kraw[i].y, dot);
+              dot = dot2_bf16(qv.z, kraw[i].z, dot);
+              dot = dot2_bf16(qv.w, kraw[i].w, dot);
+              dot = group_sum<kLanes>(dot) * q_scale;
+              sp[i] = valid ? dot : kNegBig;
+            }
+            float mx = sp[0];
+#pragma unroll
+            for (int i = 1; i < kLoads; ++i) mx = fmaxf(mx, sp[i]);
+            const float m_new = fmaxf(m_run[r], mx);
+            const float alpha = __builtin_amdgcn_exp2f(m_run[r] - m_new);
+            float psum = 0.f;
+#pragma unroll
+            for (int i = 0; i < kLoads; ++i) {
+              const bool valid = t0 + i * kTPL < geo.n_tokens;
+              sp[i] = valid ? __builtin_amdgcn_exp2f(sp[i] - m_new) : 0.f;
+              psum += sp[i];
+            }
+            l_run[r] = l_run[r] * alpha + psum;
+            m_run[r] = m_new;
+            if (__ballot(alpha != 1.f)) {  // the maximum moved somewhere in the wave (rare once warmed up)
+#pragma unroll
+              for (int c = 0; c < 8; ++c) acc[r][c] *= alpha;
+            }
+#pragma unroll
+            for (int i = 0; i < kLoads; ++i) {
+              float vf[8];
+              unpack8(vraw[i], vf);
+#pragma unroll
+              for (int c = 0; c < 8; ++c) acc[r][c] = fmaf(sp[i], vf[c], acc[r][c]);
+            }
+          }
         }
       } else {
-        issue(sl, kraw, vraw, mask_next, t0_next);
-      }
-      const uint32_t mask = mask_next;
-      const int t0 = t0_next;
-      if (kPrefetch && sl + 4 < p_hi) issue(sl + 4, knext, vnext, mask_next, t0_next);
-
-      // logits (log2 domain) of the slice's tokens for every head that wants this block
-      float sp[kG][kLoads];
-#pragma unroll
-      for (int i = 0; i < kLoads; ++i) {
-        const bool valid = t0 + i * kTPL < geo.n_tokens;
-#pragma unroll
-        for (int r = 0; r < kG; ++r) {
-          if (mask & (1u << r)) {
-            float dot = dot2_bf16(qp[r].x, kraw[i].x, 0.f);
-            dot = dot2_bf16(qp[r].y, kraw[i].y, dot);
-            dot = dot2_bf16(qp[r].z, kraw[i].z, dot);
-            dot = dot2_bf16(qp[r].w, kraw[i].w, dot);
-            dot = group_sum<kLanes>(dot) * q_scale;
-            sp[r][i] = valid ? dot : kNegBig;
+        // logits (log2 domain) of the slice's tokens for every head that wants this block
+        float sp[kG][kLoads];
+  #pragma unroll
+        for (int i = 0; i < kLoads; ++i) {
+          const bool valid = t0 + i * kTPL < geo.n_tokens;
+  #pragma unroll
+          for (int r = 0; r < kG; ++r) {
+            if (mask & (1u << r)) {
+              float dot = dot2_bf16(qp[r].x, kraw[i].x, 0.f);
+              dot = dot2_bf16(qp[r].y, kraw[i].y, dot);
+              dot = dot2_bf16(qp[r].z, kraw[i].z, dot);
+              dot = dot2_bf16(qp[r].w, kraw[i].w, dot);
+              dot = group_sum<kLanes>(dot) * q_scale;
+              sp[r][i] = valid ? dot : kNegBig;
+            }
           }
         }
-      }
-      // online-softmax update per head: new maximum, rescale, probabilities
-#pragma unroll
-      for (int r = 0; r < kG; ++r) {
-        if (mask & (1u << r)) {
-          float mx = sp[r][0];
-#pragma unroll
-          for (int i = 1; i < kLoads; ++i) mx = fmaxf(mx, sp[r][i]);
-          const float m_new = fmaxf(m_run[r], mx);
-          const float alpha = __builtin_amdgcn_exp2f(m_run[r] - m_new);
-          float psum = 0.f;
-#pragma unroll
-          for (int i = 0; i < kLoads; ++i) {
-            const bool valid = t0 + i * kTPL < geo.n_tokens;
-            sp[r][i] = valid ? __builtin_amdgcn_exp2f(sp[r][i] - m_new) : 0.f;
-            psum += sp[r][i];
-          }
-          l_run[r] = l_run[r] * alpha + psum;
-          m_run[r] = m_new;
-          if (__ballot(alpha != 1.f)) {  // the maximum moved somewhere in the wave (rare once warmed up)
-#pragma unroll
-            for (int c = 0; c < 8; ++c) acc[r][c] *= alpha;
-          }
-        }
-      }
-      // acc += p * v
-#pragma unroll
-      for (int i = 0; i < kLoads; ++i) {
-        float vf[8];
-        unpack8(vraw[i], vf);
-#pragma unroll
+        // online-softmax update per head: new maximum, rescale, probabilities
+  #pragma unroll
         for (int r = 0; r < kG; ++r) {
           if (mask & (1u << r)) {
-#pragma unroll
-            for (int c = 0; c < 8; ++c) acc[r][c] = fmaf(sp[r][i], vf[c], acc[r][c]);
+            float mx = sp[r][0];
+  #pragma unroll
+            for (int i = 1; i < kLoads; ++i) mx = fmaxf(mx, sp[r][i]);
+            const float m_new = fmaxf(m_run[r], mx);
+            const float alpha = __builtin_amdgcn_exp2f(m_run[r] - m_new);
+            float psum = 0.f;
+  #pragma unroll
+            for (int i = 0; i < kLoads; ++i) {
+              const bool valid = t0 + i * kTPL < geo.n_tokens;
+              sp[r][i] = valid ? __builtin_amdgcn_exp2f(sp[r][i] - m_new) : 0.f;
+              psum += sp[r][i];
+            }
+            l_run[r] = l_run[r] * alpha + psum;
+            m_run[r] = m_new;
+            if (__ballot(alpha != 1.f)) {  // the maximum moved somewhere in the wave (rare once warmed up)
+  #pragma unroll
+              for (int c = 0; c < 8; ++c) acc[r][c] *= alpha;
+            }
+          }
+        }
+        // acc += p * v
+  #pragma unroll
+        for (int i = 0; i < kLoads; ++i) {
+          float vf[8];
+          unpack8(vraw[i], vf);
+  #pragma unroll
+          for (int r = 0; r < kG; ++r) {
+            if (mask & (1u << r)) {
+  #pragma unroll
+              for (int c = 0; c < 8; ++c) acc[r][c] = fmaf(sp[r][i], vf[c], acc[r][c]);
+            }
           }
         }
       }
