@@ -301,7 +301,7 @@ def cpu_baseline(wl, seconds=12.0) -> dict:
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--steps", type=int, default=128)
     ap.add_argument("--warmup", type=int, default=32)
     ap.add_argument("--no-graph", action="store_true", help="time eager launches only")
     ap.add_argument("--no-extra", action="store_true", help="skip the 128K-context workloads")
@@ -396,6 +396,12 @@ def main():
             "achieved": head["attend_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": head["attend_frac_of_hbm_peak"], "traffic": profiled_traffic(head["workload"]),
             "bytes_per_launch": head["decode_unique_bytes"], "us_per_launch": head["kernel_us"]["attend"],
+        },
+        "roofline_128k": None if not others else {
+            "bound": "hbm", "kernel": "attend_kernel (split-K sparse attention)", "workload": others[0]["workload"],
+            "achieved": others[0]["attend_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": others[0]["attend_frac_of_hbm_peak"], "traffic": others[0]["attend_traffic_bytes"],
+            "bytes_per_launch": others[0]["decode_unique_bytes"], "us_per_launch": others[0]["kernel_us"]["attend"],
         },
         "stream_probe": probe,
         "workloads": others,
