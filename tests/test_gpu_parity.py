@@ -349,3 +349,44 @@ def test_random_shapes_sweep(seed):
                                        ref["kth"], ref["scores"], None)
     out = gp.decode(ref["idx"], ref["cnt"]).cpu().numpy().astype(np.float64)
     assert np.abs(out - ref["out"]).max() < TOL
+
+
+def _split_case(wl):
+    t = W.make_layer(wl)
+    ref = run_oracle(wl, t)
+    gp = GpuProblem(wl, t, k_max=ref["k_max"])
+    gp.summarize()
+    idx, cnt = gp.select()
+    exempt, differ = compare_selection(idx.cpu().numpy(), cnt.cpu().numpy(), ref["idx"], ref["cnt"], ref["gap"],
+                                       ref["kth"], ref["scores"], None)
+    out = gp.decode(ref["idx"], ref["cnt"]).cpu().numpy().astype(np.float64)
+    err = np.abs(out - ref["out"]).max()
+    print(f"  groups {wl.batch * wl.n_kv_heads}, near-tie heads {exempt}, differing {differ}, max abs err {err:.3e}",
+          flush=True)
+    assert err < TOL
+    again = gp.decode(ref["idx"], ref["cnt"]).cpu().numpy()
+    assert np.array_equal(again, out.astype(np.float32))  # claimed units do not change the bits
+
+
+def test_work_split_more_units_than_workgroups():
+    """Thousands of short (sequence, KV head) groups with little work in total: the attention kernel cuts the
+    step into group-aligned units, more of them than the launch has workgroups."""
+    rng = np.random.default_rng(77)
+    B = 600
+    wl = W.Workload(name="split_lat", n_q_heads=12, n_kv_heads=6, head_dim=64,
+                    seq_len=[int(x) for x in rng.integers(40, 400, size=B)], gran=[16] * 6, sink_tokens=16,
+                    window_tokens=32, budget_frac=np.full((B, 12), 0.3, dtype=np.float32), seed=11)
+    print(f"case=split_lat B={B}", flush=True)
+    _split_case(wl)
+
+
+def test_work_split_units_span_several_groups():
+    """The maximum number of groups (4096), each far smaller than one workgroup's share: static and claimed
+    units both span several groups and every group's partials come from more than one unit."""
+    rng = np.random.default_rng(78)
+    B = 1024
+    wl = W.Workload(name="split_span", n_q_heads=8, n_kv_heads=4, head_dim=64,
+                    seq_len=[int(x) for x in rng.integers(300, 700, size=B)], gran=[16, 32, 16, 48], sink_tokens=16,
+                    window_tokens=64, budget_frac=np.full((B, 8), 1.0, dtype=np.float32), seed=12)
+    print(f"case=split_span B={B}", flush=True)
+    _split_case(wl)
