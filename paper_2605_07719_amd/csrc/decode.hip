@@ -26,6 +26,10 @@
 
 namespace fx {
 
+#ifndef FX_PLAN_PIECE
+#define FX_PLAN_PIECE 512
+#endif
+
 __global__ __launch_bounds__(256) void plan_kernel(Params P, const int32_t* __restrict__ idx,
                                                    const int32_t* __restrict__ cnt, uint32_t* __restrict__ uni,
                                                    int32_t* __restrict__ ucount, int union_cap,
@@ -47,10 +51,11 @@ __global__ __launch_bounds__(256) void plan_kernel(Params P, const int32_t* __re
   const int n_words = (geo.n_blocks + 3) >> 2;
   for (int w = tid; w < n_words; w += 256) mask_words[w] = 0u;
   __syncthreads();
-  // The heads' index lists are cut into pieces of 512 entries and the pieces are dealt to the 4 waves
-  // round-robin, so short lists of different heads are walked concurrently and a long list is shared by
-  // all waves; a lane keeps eight index loads in flight before the LDS atomics that consume them.
+  // The heads' index lists are cut into pieces of FX_PLAN_PIECE entries and the pieces are dealt to the 4
+  // waves round-robin, so short lists of different heads are walked concurrently and a long list is shared
+  // by all waves; a lane keeps all index loads of a piece in flight before the LDS atomics that consume them.
   {
+    constexpr int kPiece = FX_PLAN_PIECE;
     const int wave = tid >> 6, lane = tid & 63;
     int piece_no = 0;
 #pragma unroll
@@ -59,44 +64,70 @@ __global__ __launch_bounds__(256) void plan_kernel(Params P, const int32_t* __re
       const int64_t slot = (int64_t)b * P.n_q_heads + j * P.group + r;
       const int c = counts[r];
       const int32_t* list = idx + slot * P.k_max;
-      for (int base = 0; base < c; base += 512, ++piece_no) {
+      for (int base = 0; base < c; base += kPiece, ++piece_no) {
         if ((piece_no & 3) != wave) continue;
-        int i[8];
+        int i[kPiece / 64];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < kPiece / 64; ++u) {
           const int e = base + u * 64 + lane;
           i[u] = e < c ? list[e] : -1;
         }
 #pragma unroll
-        for (int u = 0; u < 8; ++u)
+        for (int u = 0; u < kPiece / 64; ++u)
           if (i[u] >= 0 && i[u] < geo.n_blocks) atomicOr(&mask_words[i[u] >> 2], (1u << r) << ((i[u] & 3) * 8));
       }
     }
   }
   __syncthreads();
-  // ordered compaction: thread t owns the consecutive blocks [t * per, (t + 1) * per), so one block
-  // scan of the per-thread counts gives every thread its write position
+  // Ordered compaction in two sweeps.  A wave owns a contiguous quarter of the blocks and walks it 64
+  // blocks at a time: the first sweep counts the kept blocks (ballot + popcount, no barrier), one barrier
+  // exchanges the four wave totals, the second sweep writes each kept block at wave base + running count
+  // + its rank inside the ballot, so every store instruction writes one contiguous run of entries.
   const uint32_t all = (1u << P.group) - 1u;
-  const int per = (geo.n_blocks + 255) >> 8;
-  const int i0 = min(tid * per, geo.n_blocks), i1 = min(i0 + per, geo.n_blocks);
-  auto mask_of = [&](int i) -> uint32_t {
-    if (i < geo.n_sink || i >= geo.w0) return all;
-    const uint32_t m = (mask_words[i >> 2] >> ((i & 3) * 8)) & 255u;
-    return (P.group_union && m) ? all : m;
+  const bool as_union = P.group_union != 0;
+  // head mask of block i, 0 past `end`; branch-free with an unconditional (clamped) LDS read so that the
+  // reads of an unrolled step are all in flight together
+  auto mask_of = [&](int i, int end) -> uint32_t {
+    const int ic = min(i, geo.n_blocks - 1);
+    uint32_t m = (mask_words[ic >> 2] >> ((ic & 3) * 8)) & 255u;
+    m = (as_union && m != 0u) ? all : m;
+    m = (ic < geo.n_sink || ic >= geo.w0) ? all : m;
+    return i < end ? m : 0u;
   };
-  int mine = 0;
-  for (int i = i0; i < i1; ++i) mine += mask_of(i) != 0u;
-  const int incl = block_incl_scan(mine, scratch);
-  int pos = incl - mine;
+  const int wave = tid >> 6, lane = tid & 63;
+  const int per_wave = ((geo.n_blocks + 255) >> 8) << 6;  // a multiple of 64; 4 * per_wave >= n_blocks
+  const int w_lo = min(wave * per_wave, geo.n_blocks), w_hi = min(w_lo + per_wave, geo.n_blocks);
+  // four 64-block steps per iteration keep four LDS reads in flight
+  int count = 0;
+  for (int base = w_lo; base < w_hi; base += 256) {
+    uint32_t m[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) m[u] = mask_of(base + u * 64 + lane, w_hi);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) count += __popcll(__ballot(m[u] != 0u));
+  }
+  if (lane == 0) scratch[wave] = count;
+  __syncthreads();
+  int pos = 0, total = 0;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    if (w < wave) pos += scratch[w];
+    total += scratch[w];
+  }
   uint32_t* dst = uni + (int64_t)grp * union_cap;
-  for (int i = i0; i < i1; ++i) {
-    const uint32_t m = mask_of(i);
-    if (m != 0u) {
-      if (pos < union_cap) dst[pos] = ((uint32_t)i << 8) | m;
-      ++pos;
+  for (int base = w_lo; base < w_hi; base += 256) {
+    uint32_t m[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) m[u] = mask_of(base + u * 64 + lane, w_hi);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const unsigned long long kept = __ballot(m[u] != 0u);
+      const int at = pos + __popcll(kept & ((1ull << lane) - 1ull));
+      if (m[u] != 0u && at < union_cap) dst[at] = ((uint32_t)(base + u * 64 + lane) << 8) | m[u];
+      pos += __popcll(kept);
     }
   }
-  if (tid == 255) ucount[grp] = incl < union_cap ? incl : union_cap;
+  if (tid == 0) ucount[grp] = total < union_cap ? total : union_cap;
   if (grp == 0 && tid == 0) *claim_counter = 0;  // the attention kernel that follows claims units from it
 }
 
