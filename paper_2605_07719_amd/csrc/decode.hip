@@ -30,12 +30,18 @@ namespace fx {
 #define FX_PLAN_PIECE 512
 #endif
 
-__global__ __launch_bounds__(256) void plan_kernel(Params P, const int32_t* __restrict__ idx,
+#ifndef FX_PLAN_WAVES
+#define FX_PLAN_WAVES 8
+#endif
+constexpr int kPlanWaves = FX_PLAN_WAVES;  // a group is one workgroup's job; 8 waves measured best (4: long lists serialise, 16: slow start)
+constexpr int kPlanThreads = 64 * kPlanWaves;
+
+__global__ __launch_bounds__(kPlanThreads) void plan_kernel(Params P, const int32_t* __restrict__ idx,
                                                    const int32_t* __restrict__ cnt, uint32_t* __restrict__ uni,
                                                    int32_t* __restrict__ ucount, int union_cap,
                                                    int32_t* __restrict__ claim_counter) {
   extern __shared__ uint32_t mask_words[];  // one byte of head mask per block, 4 blocks per word
-  __shared__ int scratch[4];
+  __shared__ int scratch[kPlanWaves];
   const int b = blockIdx.y, j = blockIdx.x, tid = threadIdx.x;
   const int grp = b * P.n_kv_heads + j;
   int counts[kMaxGroup];  // requested before the geometry so they arrive together with the sequence length
@@ -49,9 +55,9 @@ __global__ __launch_bounds__(256) void plan_kernel(Params P, const int32_t* __re
   }
   const Geo geo = geometry(P, b, j);
   const int n_words = (geo.n_blocks + 3) >> 2;
-  for (int w = tid; w < n_words; w += 256) mask_words[w] = 0u;
+  for (int w = tid; w < n_words; w += kPlanThreads) mask_words[w] = 0u;
   __syncthreads();
-  // The heads' index lists are cut into pieces of FX_PLAN_PIECE entries and the pieces are dealt to the 4
+  // The heads' index lists are cut into pieces of FX_PLAN_PIECE entries and the pieces are dealt to the
   // waves round-robin, so short lists of different heads are walked concurrently and a long list is shared
   // by all waves; a lane keeps all index loads of a piece in flight before the LDS atomics that consume them.
   {
@@ -65,7 +71,7 @@ __global__ __launch_bounds__(256) void plan_kernel(Params P, const int32_t* __re
       const int c = counts[r];
       const int32_t* list = idx + slot * P.k_max;
       for (int base = 0; base < c; base += kPiece, ++piece_no) {
-        if ((piece_no & 3) != wave) continue;
+        if (piece_no % kPlanWaves != wave) continue;
         int i[kPiece / 64];
 #pragma unroll
         for (int u = 0; u < kPiece / 64; ++u) {
@@ -79,9 +85,9 @@ __global__ __launch_bounds__(256) void plan_kernel(Params P, const int32_t* __re
     }
   }
   __syncthreads();
-  // Ordered compaction in two sweeps.  A wave owns a contiguous quarter of the blocks and walks it 64
+  // Ordered compaction in two sweeps.  A wave owns a contiguous share of the blocks and walks it 64
   // blocks at a time: the first sweep counts the kept blocks (ballot + popcount, no barrier), one barrier
-  // exchanges the four wave totals, the second sweep writes each kept block at wave base + running count
+  // exchanges the wave totals, the second sweep writes each kept block at wave base + running count
   // + its rank inside the ballot, so every store instruction writes one contiguous run of entries.
   const uint32_t all = (1u << P.group) - 1u;
   const bool as_union = P.group_union != 0;
@@ -95,7 +101,7 @@ __global__ __launch_bounds__(256) void plan_kernel(Params P, const int32_t* __re
     return i < end ? m : 0u;
   };
   const int wave = tid >> 6, lane = tid & 63;
-  const int per_wave = ((geo.n_blocks + 255) >> 8) << 6;  // a multiple of 64; 4 * per_wave >= n_blocks
+  const int per_wave = (geo.n_blocks + kPlanThreads - 1) / kPlanThreads * 64;  // a multiple of 64; all waves together cover n_blocks
   const int w_lo = min(wave * per_wave, geo.n_blocks), w_hi = min(w_lo + per_wave, geo.n_blocks);
   // four 64-block steps per iteration keep four LDS reads in flight
   int count = 0;
@@ -110,7 +116,7 @@ __global__ __launch_bounds__(256) void plan_kernel(Params P, const int32_t* __re
   __syncthreads();
   int pos = 0, total = 0;
 #pragma unroll
-  for (int w = 0; w < 4; ++w) {
+  for (int w = 0; w < kPlanWaves; ++w) {
     if (w < wave) pos += scratch[w];
     total += scratch[w];
   }
@@ -624,7 +630,7 @@ hipError_t launch_decode(const Params& P, const void* q, const void* K, const vo
   const size_t plan_lds = (size_t)((P.nb_stride + 3) / 4) * sizeof(uint32_t);
   {
     ScopedSlot prof(kSlotPlan, stream);
-    hipLaunchKernelGGL(plan_kernel, dim3(P.n_kv_heads, P.batch), dim3(256), plan_lds, stream, P, idx, cnt, uni,
+    hipLaunchKernelGGL(plan_kernel, dim3(P.n_kv_heads, P.batch), dim3(kPlanThreads), plan_lds, stream, P, idx, cnt, uni,
                        ucount, W.union_cap, sched + P.batch * P.n_kv_heads + 5);
   }
   hipError_t e = hipGetLastError();
