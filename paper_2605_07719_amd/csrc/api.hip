@@ -179,7 +179,7 @@ fx_status fx_select(const fx_layout* layout, const void* q, const void* summarie
   if ((budget_frac == nullptr) == (budget_blocks == nullptr)) return FX_ERR_INVALID_ARG;
   if (!aligned16(q) || !aligned16(summaries) || !aligned16(workspace)) return FX_ERR_INVALID_ARG;
   if (workspace_bytes < fx::carve_select(P).total) return FX_ERR_WORKSPACE_TOO_SMALL;
-  return fx::launch_select(P, q, summaries, budget_frac, budget_blocks, idx, cnt, workspace,
+  return fx::launch_select(P, q, summaries, budget_frac, budget_blocks, idx, cnt, workspace, compute_units(),
                            static_cast<hipStream_t>(stream)) == hipSuccess
              ? FX_OK
              : FX_ERR_HIP;

@@ -106,7 +106,7 @@ hipError_t launch_summarize(const Params& P, const void* K, void* S, const int32
                             hipStream_t stream);
 hipError_t launch_coarsen(const Params& Pf, const Params& Pc, const void* Sf, void* Sc, hipStream_t stream);
 hipError_t launch_select(const Params& P, const void* q, const void* S, const float* budget_frac,
-                         const int32_t* budget_blocks, int32_t* idx, int32_t* cnt, void* workspace,
+                         const int32_t* budget_blocks, int32_t* idx, int32_t* cnt, void* workspace, int n_cu,
                          hipStream_t stream);
 hipError_t launch_decode(const Params& P, const void* q, const void* K, const void* V, const int32_t* idx,
                          const int32_t* cnt, float* out, void* workspace, int n_cu, hipStream_t stream);

@@ -56,38 +56,32 @@ __device__ __forceinline__ float key32_to_float(uint32_t k) {
 // The summaries are loaded straight into the B layout (each lane 16 bytes of its own row).  Staging
 // them through LDS with fully coalesced loads was measured to be about twice slower, and loading with
 // four neighbouring lanes per row followed by a wave-wide permutation made no difference.
-// A wave walks `tiles_per_wave` consecutive tiles of 16 candidates, requesting the next tile's rows
-// before it multiplies the current one.  The magnitude sums are reduced to one maximum per tile and
-// head before they leave the kernel (the selection only needs their maximum per head).  The scores
-// are stored tile-major, [sequence][KV head][tile][head of the group][16], so that a wave's stores for
-// a tile form one contiguous run of G * 64 bytes (scattered 64-byte pieces cost ~10% of the kernel).
+// The magnitude sums are reduced to one maximum per tile and head before they leave the kernel (the
+// selection only needs their maximum per head).  The scores are stored tile-major,
+// [sequence][KV head][tile][head of the group][16], so that a wave's stores for a tile form one
+// contiguous run of G * 64 bytes (scattered 64-byte pieces cost ~10% of the kernel).
+
+// One wave scores tiles [tile_first, tile_end) of group (b, j): it requests the next tile's rows before it
+// multiplies the current one.  `rows` points at the group's first candidate row.
 template <int kD>
-__global__ __launch_bounds__(256) void score_kernel(Params P, const uint16_t* __restrict__ q,
-                                                    const uint16_t* __restrict__ S, float* __restrict__ approx,
-                                                    float* __restrict__ mag_tile, const float* __restrict__ budget_frac,
-                                                    const int32_t* __restrict__ budget_blocks, int tiles_per_wave,
-                                                    int mag_stride) {
+__device__ __forceinline__ void score_tiles(const Params& P, const uint16_t* __restrict__ q,
+                                            const uint16_t* __restrict__ rows_base, int n_cand, int b, int j,
+                                            int tile_first, int tile_end, float* __restrict__ approx,
+                                            float* __restrict__ mag_tile, int mag_stride, int lane) {
   constexpr int kRow = 2 * kD;       // elements of one [mn | mx] row
   constexpr int kSlabs = kRow / 32;  // MFMA k-steps per row
-  const int b = blockIdx.z, j = blockIdx.y;
-  const Geo geo = geometry(P, b, j);
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n = lane & 15, r = lane >> 4;
-  const int tile_first = (blockIdx.x * 4 + wave) * tiles_per_wave;
-  if (tile_first * 16 >= geo.n_cand) return;
-  {
-    // a group whose heads all have budget 0 (streaming heads, Sec. 3.2) needs no scores: its summaries
-    // are not read at all
-    bool any = false;
-    for (int h = 0; h < P.group; ++h) {
-      const int64_t slot = (int64_t)b * P.n_q_heads + j * P.group + h;
-      any |= budget_blocks ? budget_blocks[slot] > 0 : budget_frac[slot] > 0.f;
-    }
-    if (!any) return;
-  }
-  const int tile_end = min(tile_first + tiles_per_wave, (geo.n_cand + 15) >> 4);
+  const uint16_t* rows = rows_base + r * 8;
+  uint4 cur[kSlabs], nxt[kSlabs];
+  auto fetch = [&](int tile, uint4* dst) {
+    const int cand = min(tile * 16 + n, n_cand - 1);  // clamped: stays inside the candidates
+    const uint16_t* p = rows + (int64_t)cand * kRow;
+#pragma unroll
+    for (int s = 0; s < kSlabs; ++s) dst[s] = *reinterpret_cast<const uint4*>(p + 32 * s);
+  };
+  fetch(tile_first, nxt);
 
-  // A operand, built once per wave from q with bit operations on the packed bf16 pairs:
+  // A operand, built once per group from q with bit operations on the packed bf16 pairs:
   // q- keeps the negative elements, q+ the others; the magnitude rows drop the sign.
   uint4 a_op[kSlabs];
   {
@@ -110,15 +104,6 @@ __global__ __launch_bounds__(256) void score_kernel(Params P, const uint16_t* __
     }
   }
 
-  const uint16_t* rows = S + (P.sum_base[(int64_t)b * P.n_kv_heads + j] + geo.n_sink) * (int64_t)kRow + r * 8;
-  uint4 cur[kSlabs], nxt[kSlabs];
-  auto fetch = [&](int tile, uint4* dst) {
-    const int cand = min(tile * 16 + n, geo.n_cand - 1);  // clamped: stays inside the candidates
-    const uint16_t* p = rows + (int64_t)cand * kRow;
-#pragma unroll
-    for (int s = 0; s < kSlabs; ++s) dst[s] = *reinterpret_cast<const uint4*>(p + 32 * s);
-  };
-  fetch(tile_first, nxt);
   const int head_row = (4 * r) & 7;  // this lane's D rows are heads head_row .. head_row + 3
   for (int tile = tile_first; tile < tile_end; ++tile) {
 #pragma unroll
@@ -135,7 +120,7 @@ __global__ __launch_bounds__(256) void score_kernel(Params P, const uint16_t* __
                                                     __builtin_bit_cast(bf16x8_t, va), d_a, 0, 0, 0);
     }
     const int cand = tile * 16 + n;
-    if (r < 2 && cand < geo.n_cand) {
+    if (r < 2 && cand < n_cand) {
 #pragma unroll
       for (int i = 0; i < 4; ++i)
         if (head_row + i < P.group)
@@ -152,6 +137,112 @@ __global__ __launch_bounds__(256) void score_kernel(Params P, const uint16_t* __
       if (r >= 2 && n == 0 && head_row + i < P.group)
         mag_tile[((int64_t)b * P.n_q_heads + j * P.group + head_row + i) * mag_stride + tile] = m;
     }
+  }
+}
+
+// Does any head of group (b, j) select blocks at all?  A group of streaming heads (Sec. 3.2: budget 0)
+// needs no scores and its summaries are never read.  Unrolled so that the loads go out together.
+__device__ __forceinline__ bool group_selects(const Params& P, const float* __restrict__ budget_frac,
+                                              const int32_t* __restrict__ budget_blocks, int b, int j) {
+  bool any = false;
+#pragma unroll
+  for (int h = 0; h < kMaxGroup; ++h) {
+    if (h < P.group) {
+      const int64_t slot = (int64_t)b * P.n_q_heads + j * P.group + h;
+      any |= budget_blocks ? budget_blocks[slot] > 0 : budget_frac[slot] > 0.f;
+    }
+  }
+  return any;
+}
+
+// Small steps (at most one tile per wave slot of the chip): the grid enumerates (sequence, KV head, tile
+// range) directly and a wave needs nothing but its own group's length, so its first loads go out at once.
+template <int kD>
+__global__ __launch_bounds__(256) void score_grid_kernel(Params P, const uint16_t* __restrict__ q,
+                                                         const uint16_t* __restrict__ S, float* __restrict__ approx,
+                                                         float* __restrict__ mag_tile,
+                                                         const float* __restrict__ budget_frac,
+                                                         const int32_t* __restrict__ budget_blocks, int mag_stride) {
+  const int b = blockIdx.z, j = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const Geo geo = geometry(P, b, j);
+  const int tile = blockIdx.x * 4 + wave;
+  if (tile * 16 >= geo.n_cand) return;  // whole wave leaves
+  if (!group_selects(P, budget_frac, budget_blocks, b, j)) return;
+  const uint16_t* rows = S + (P.sum_base[(int64_t)b * P.n_kv_heads + j] + geo.n_sink) * (int64_t)(2 * kD);
+  score_tiles<kD>(P, q, rows, geo.n_cand, b, j, tile, tile + 1, approx, mag_tile, mag_stride, lane);
+}
+
+// Larger steps: the tiles of all groups that need scores form one global tile sequence (its prefix over
+// the groups is computed by every workgroup from the sequence lengths and budgets); every wave of the
+// launch walks an equal contiguous share of it and rebuilds its A operand where the share crosses into
+// the next group.  Ragged batches, mixed block sizes and streaming groups therefore cost nothing in
+// balance (a grid over the longest sequence leaves most workgroups of a short one without work).
+template <int kD>
+__global__ __launch_bounds__(256) void score_stream_kernel(Params P, const uint16_t* __restrict__ q,
+                                                           const uint16_t* __restrict__ S, float* __restrict__ approx,
+                                                           float* __restrict__ mag_tile,
+                                                           const float* __restrict__ budget_frac,
+                                                           const int32_t* __restrict__ budget_blocks, int mag_stride) {
+  // per group, filled by the prologue so that a wave entering a group starts its first loads at once:
+  extern __shared__ long long s_rowbase[];  // [n_groups] first candidate's row (in blocks) inside the summaries
+  __shared__ int s_scan[4];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n_groups = P.batch * P.n_kv_heads;
+  int* s_tiles = reinterpret_cast<int*>(s_rowbase + n_groups);  // [n_groups + 1] exclusive prefix of tiles
+  int* s_ncand = s_tiles + n_groups + 1;                        // [n_groups] candidates
+  {
+    auto tiles_of = [&](int g) -> int {
+      const int b = g / P.n_kv_heads, j = g - b * P.n_kv_heads;
+      const bool any = group_selects(P, budget_frac, budget_blocks, b, j);
+      const Geo geo = geometry(P, b, j);
+      s_ncand[g] = geo.n_cand;
+      s_rowbase[g] = P.sum_base[g] + geo.n_sink;
+      return any ? (geo.n_cand + 15) >> 4 : 0;
+    };
+    const int per = (n_groups + 255) / 256;
+    const int g_lo = min(tid * per, n_groups), g_hi = min(g_lo + per, n_groups);
+    int local = 0;
+    for (int g = g_lo; g < g_hi; ++g) {
+      const int c = tiles_of(g);
+      s_tiles[g] = c;  // replaced by the prefix below (same thread)
+      local += c;
+    }
+    const int incl = block_incl_scan(local, s_scan);
+    int run = incl - local;
+    for (int g = g_lo; g < g_hi; ++g) {
+      const int c = s_tiles[g];
+      s_tiles[g] = run;
+      run += c;
+    }
+    if (tid == 255) s_tiles[n_groups] = incl;
+  }
+  __syncthreads();
+  const int total_tiles = s_tiles[n_groups];
+  const int n_waves = gridDim.x * 4;
+  const int share = (total_tiles + n_waves - 1) / n_waves;
+  int t = (blockIdx.x * 4 + wave) * share;
+  const int t_end = min(t + share, total_tiles);
+  if (t >= t_end) return;  // whole wave leaves
+
+  int grp;  // group of tile t: the last g with s_tiles[g] <= t (groups without tiles are skipped)
+  {
+    int lo = 0, hi = n_groups - 1;
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (s_tiles[mid] <= t) lo = mid; else hi = mid - 1;
+    }
+    grp = lo;
+  }
+  while (t < t_end) {
+    const int b = grp / P.n_kv_heads, j = grp - b * P.n_kv_heads;
+    const int tile_first = t - s_tiles[grp];
+    const int tile_end = min(t_end, s_tiles[grp + 1]) - s_tiles[grp];
+    score_tiles<kD>(P, q, S + s_rowbase[grp] * (int64_t)(2 * kD), s_ncand[grp], b, j, tile_first, tile_end, approx,
+                    mag_tile, mag_stride, lane);
+    t = s_tiles[grp] + tile_end;
+    do ++grp; while (grp < n_groups && s_tiles[grp + 1] <= t);  // next group that has tiles
   }
 }
 
@@ -608,8 +699,22 @@ __global__ __launch_bounds__(256) void topk_reg_kernel(Params P, TopkArgs A) {
 
 float select_error_gamma() { return kGamma; }
 
+// Resident workgroups of the score kernel per CU, queried once per head size.
+static int score_wg_per_cu(int head_dim, size_t lds) {
+  static int cached[2] = {0, 0};
+  int& c = cached[head_dim == 128 ? 1 : 0];
+  if (c == 0) {
+    int n = 0;
+    const hipError_t e = head_dim == 128 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, score_stream_kernel<128>, 256, lds)
+                                         : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, score_stream_kernel<64>, 256, lds);
+    if (e != hipSuccess || n < 1) n = 1;
+    c = n > 8 ? 8 : n;
+  }
+  return c;
+}
+
 hipError_t launch_select(const Params& P, const void* q, const void* S, const float* budget_frac,
-                         const int32_t* budget_blocks, int32_t* idx, int32_t* cnt, void* workspace,
+                         const int32_t* budget_blocks, int32_t* idx, int32_t* cnt, void* workspace, int n_cu,
                          hipStream_t stream) {
   const SelectWorkspace W = carve_select(P);
   char* ws = static_cast<char*>(workspace);
@@ -619,18 +724,24 @@ hipError_t launch_select(const Params& P, const void* q, const void* S, const fl
   const int mag_stride = W.mag_stride;
   {
     ScopedSlot prof(kSlotScore, stream);
-    // tiles of 16 candidates per wave: enough workgroups to fill the chip first, then longer walks
-    const int64_t total_tiles = (int64_t)P.batch * P.n_kv_heads * mag_stride;
-    int tiles_per_wave = (int)(total_tiles / 4096);
-    tiles_per_wave = tiles_per_wave < 1 ? 1 : (tiles_per_wave > 8 ? 8 : tiles_per_wave);
-    const int cand_per_wg = 4 * tiles_per_wave * 16;
-    dim3 sgrid((P.nb_stride + cand_per_wg - 1) / cand_per_wg, P.n_kv_heads, P.batch);
-    if (P.head_dim == 128)
-      hipLaunchKernelGGL(score_kernel<128>, sgrid, dim3(256), 0, stream, P, (const uint16_t*)q, (const uint16_t*)S,
-                         approx, mag, budget_frac, budget_blocks, tiles_per_wave, mag_stride);
-    else
-      hipLaunchKernelGGL(score_kernel<64>, sgrid, dim3(256), 0, stream, P, (const uint16_t*)q, (const uint16_t*)S,
-                         approx, mag, budget_frac, budget_blocks, tiles_per_wave, mag_stride);
+    const size_t lds = (size_t)P.batch * P.n_kv_heads * (sizeof(long long) + 2 * sizeof(int)) + sizeof(int);
+    const int64_t max_tiles = (int64_t)P.batch * P.n_kv_heads * mag_stride;
+    const int64_t slots = (int64_t)n_cu * score_wg_per_cu(P.head_dim, lds);  // resident workgroups of the chip
+    if (max_tiles <= 4 * slots) {  // at most one tile per wave slot
+      const dim3 grid((mag_stride + 3) / 4, P.n_kv_heads, P.batch);
+      if (P.head_dim == 128)
+        hipLaunchKernelGGL(score_grid_kernel<128>, grid, dim3(256), 0, stream, P, (const uint16_t*)q,
+                           (const uint16_t*)S, approx, mag, budget_frac, budget_blocks, mag_stride);
+      else
+        hipLaunchKernelGGL(score_grid_kernel<64>, grid, dim3(256), 0, stream, P, (const uint16_t*)q,
+                           (const uint16_t*)S, approx, mag, budget_frac, budget_blocks, mag_stride);
+    } else if (P.head_dim == 128) {
+      hipLaunchKernelGGL(score_stream_kernel<128>, dim3((unsigned)slots), dim3(256), lds, stream, P,
+                         (const uint16_t*)q, (const uint16_t*)S, approx, mag, budget_frac, budget_blocks, mag_stride);
+    } else {
+      hipLaunchKernelGGL(score_stream_kernel<64>, dim3((unsigned)slots), dim3(256), lds, stream, P,
+                         (const uint16_t*)q, (const uint16_t*)S, approx, mag, budget_frac, budget_blocks, mag_stride);
+    }
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
