@@ -341,8 +341,8 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
 #pragma unroll
       for (int i = 0; i < kLoads; ++i) {
         const int64_t row = (int64_t)min(t0 + i * kTPL, geo.n_tokens - 1) * P.token_stride;
-        kraw[i] = *reinterpret_cast<const uint4*>(Kb + row);
-        vraw[i] = *reinterpret_cast<const uint4*>(Vb + row);
+        kraw[i] = stream_load16(Kb + row);
+        vraw[i] = stream_load16(Vb + row);
       }
 
       if constexpr (kHeadMajor) {

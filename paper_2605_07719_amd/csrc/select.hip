@@ -77,7 +77,7 @@ __device__ __forceinline__ void score_tiles(const Params& P, const uint16_t* __r
     const int cand = min(tile * 16 + n, n_cand - 1);  // clamped: stays inside the candidates
     const uint16_t* p = rows + (int64_t)cand * kRow;
 #pragma unroll
-    for (int s = 0; s < kSlabs; ++s) dst[s] = *reinterpret_cast<const uint4*>(p + 32 * s);
+    for (int s = 0; s < kSlabs; ++s) dst[s] = *reinterpret_cast<const uint4*>(p + 32 * s);  // (plain: two loads share each 128-byte line)
   };
   fetch(tile_first, nxt);
 

@@ -32,14 +32,14 @@ __global__ __launch_bounds__(256) void summarize_kernel(Params P, const uint16_t
 
   float mn[8], mx[8];
   {
-    uint4 r = *reinterpret_cast<const uint4*>(src + (int64_t)t_lo * P.token_stride);
+    uint4 r = stream_load16(src + (int64_t)t_lo * P.token_stride);
     unpack8(r, mn);
 #pragma unroll
     for (int c = 0; c < 8; ++c) mx[c] = mn[c];
   }
 #pragma unroll 4
   for (int t = t_lo + 1; t < t_hi; ++t) {
-    uint4 r = *reinterpret_cast<const uint4*>(src + (int64_t)t * P.token_stride);
+    uint4 r = stream_load16(src + (int64_t)t * P.token_stride);
     float x[8];
     unpack8(r, x);
 #pragma unroll
@@ -72,12 +72,12 @@ __global__ __launch_bounds__(256) void coarsen_kernel(Params Pf, Params Pc, cons
   const int f_hi = min(f_lo + ratio, gf.n_blocks);
   const uint16_t* src = Sf + Pf.sum_base[(int64_t)b * Pf.n_kv_heads + j] * 2 * (int64_t)kD + chunk * 8;
   float mn[8], mx[8];
-  unpack8(*reinterpret_cast<const uint4*>(src + (int64_t)f_lo * 2 * kD), mn);
-  unpack8(*reinterpret_cast<const uint4*>(src + (int64_t)f_lo * 2 * kD + kD), mx);
+  unpack8(stream_load16(src + (int64_t)f_lo * 2 * kD), mn);
+  unpack8(stream_load16(src + (int64_t)f_lo * 2 * kD + kD), mx);
   for (int f = f_lo + 1; f < f_hi; ++f) {
     float a[8], c[8];
-    unpack8(*reinterpret_cast<const uint4*>(src + (int64_t)f * 2 * kD), a);
-    unpack8(*reinterpret_cast<const uint4*>(src + (int64_t)f * 2 * kD + kD), c);
+    unpack8(stream_load16(src + (int64_t)f * 2 * kD), a);
+    unpack8(stream_load16(src + (int64_t)f * 2 * kD + kD), c);
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
       mn[t] = fminf(mn[t], a[t]);
