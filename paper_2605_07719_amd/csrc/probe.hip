@@ -10,6 +10,18 @@ namespace {
 
 constexpr int kUnroll = 8;
 
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+template <bool kNonTemporal>
+__device__ __forceinline__ uint4 load16(const uint4* p) {
+  if (kNonTemporal) {
+    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+  }
+  return *p;
+}
+
+template <bool kNonTemporal>
 __global__ __launch_bounds__(256) void probe_read_kernel(const uint4* __restrict__ src, size_t n16,
                                                          uint32_t* __restrict__ sink) {
   const size_t stride = (size_t)gridDim.x * 256;
@@ -18,14 +30,14 @@ __global__ __launch_bounds__(256) void probe_read_kernel(const uint4* __restrict
   for (; i + (kUnroll - 1) * stride < n16; i += kUnroll * stride) {
     uint4 v[kUnroll];
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) v[u] = src[i + u * stride];
+    for (int u = 0; u < kUnroll; ++u) v[u] = load16<kNonTemporal>(src + i + u * stride);
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
       acc.x ^= v[u].x; acc.y ^= v[u].y; acc.z ^= v[u].z; acc.w ^= v[u].w;
     }
   }
   for (; i < n16; i += stride) {
-    uint4 v = src[i];
+    uint4 v = load16<kNonTemporal>(src + i);
     acc.x ^= v.x; acc.y ^= v.y; acc.z ^= v.z; acc.w ^= v.w;
   }
   // data-dependent, practically never true: keeps the loads alive without a store per thread
@@ -54,8 +66,17 @@ extern "C" {
 
 fx_status fx_probe_read(const void* src, size_t bytes, void* sink, int wg_per_cu, void* stream) {
   if (!src || !sink || bytes < 16 || (reinterpret_cast<uintptr_t>(src) & 15u)) return FX_ERR_INVALID_ARG;
-  hipLaunchKernelGGL(probe_read_kernel, dim3(grid_for(wg_per_cu)), dim3(256), 0, static_cast<hipStream_t>(stream),
-                     static_cast<const uint4*>(src), bytes / 16, static_cast<uint32_t*>(sink));
+  hipLaunchKernelGGL(probe_read_kernel<false>, dim3(grid_for(wg_per_cu)), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), static_cast<const uint4*>(src), bytes / 16,
+                     static_cast<uint32_t*>(sink));
+  return hipGetLastError() == hipSuccess ? FX_OK : FX_ERR_HIP;
+}
+
+fx_status fx_probe_read_streaming(const void* src, size_t bytes, void* sink, int wg_per_cu, void* stream) {
+  if (!src || !sink || bytes < 16 || (reinterpret_cast<uintptr_t>(src) & 15u)) return FX_ERR_INVALID_ARG;
+  hipLaunchKernelGGL(probe_read_kernel<true>, dim3(grid_for(wg_per_cu)), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), static_cast<const uint4*>(src), bytes / 16,
+                     static_cast<uint32_t*>(sink));
   return hipGetLastError() == hipSuccess ? FX_OK : FX_ERR_HIP;
 }
 

@@ -19,7 +19,7 @@ LIB_PATH = os.environ.get("FLUXION_LIB", os.path.join(_HERE, "libfluxion.so"))  
 
 EXPORTS = (
     "fx_status_string", "fx_summarize", "fx_select_workspace_bytes", "fx_select", "fx_decode_workspace_bytes",
-    "fx_sparse_decode", "fx_profile_enable", "fx_profile_read", "fx_probe_read", "fx_probe_copy", "fx_select_workspace_view", "fx_choose_granularity",
+    "fx_sparse_decode", "fx_profile_enable", "fx_profile_read", "fx_probe_read", "fx_probe_read_streaming", "fx_probe_copy", "fx_select_workspace_view", "fx_choose_granularity",
     "fx_coarsen_summaries", "fx_summarize_append", "fx_sparse_decode_union",
 )
 
@@ -81,6 +81,8 @@ def lib() -> ctypes.CDLL:
         L.fx_profile_read.argtypes = [ctypes.c_void_p, ctypes.c_int]
         L.fx_probe_read.restype = ctypes.c_int
         L.fx_probe_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
+        L.fx_probe_read_streaming.restype = ctypes.c_int
+        L.fx_probe_read_streaming.argtypes = L.fx_probe_read.argtypes
         L.fx_probe_copy.restype = ctypes.c_int
         L.fx_probe_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p]
         _lib = L
@@ -274,6 +276,12 @@ def probe_read(src: torch.Tensor, sink: torch.Tensor, wg_per_cu: int = 8, stream
     """fx_probe_read: plain streaming read of the whole tensor (measurement aid)."""
     _check(lib().fx_probe_read(_dptr(src), src.numel() * src.element_size(), _dptr(sink), wg_per_cu, _stream(stream)),
            "fx_probe_read")
+
+
+def probe_read_streaming(src: torch.Tensor, sink: torch.Tensor, wg_per_cu: int = 8, stream=None) -> None:
+    """fx_probe_read_streaming: the same read with non-temporal loads (measurement aid)."""
+    _check(lib().fx_probe_read_streaming(_dptr(src), src.numel() * src.element_size(), _dptr(sink), wg_per_cu,
+                                         _stream(stream)), "fx_probe_read_streaming")
 
 
 def probe_copy(dst: torch.Tensor, src: torch.Tensor, wg_per_cu: int = 8, stream=None) -> None:

@@ -117,6 +117,7 @@ def test_bad_arguments_are_rejected_before_any_launch():
     # measurement aids
     assert lib.fx_profile_read(None, 5) == INV
     assert lib.fx_probe_read(None, 1024, p, 4, None) == INV
+    assert lib.fx_probe_read_streaming(None, 1024, p, 4, None) == INV
     assert lib.fx_probe_copy(p, p, 8, 4, None) == INV
 
 
