@@ -102,18 +102,21 @@ __device__ __forceinline__ float group_sum(float x) {
   return x;
 }
 
-// Block-wide exclusive prefix count of a predicate for a 256-thread workgroup (4 waves).
-// `scratch` is 4 ints of LDS reserved for this call site; two barriers per call.
+constexpr int kMaxWaves = 16;  // waves of the largest workgroup (1024 threads)
+
+// Block-wide exclusive prefix count of a predicate over a workgroup of kW waves.
+// `scratch` is kW ints of LDS reserved for this call site; two barriers per call.
+template <int kW = 4>
 __device__ __forceinline__ int block_excl_count(bool flag, int* scratch, int& total) {
   unsigned long long ball = __ballot(flag);
-  int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int before = __popcll(ball & ((1ull << lane) - 1ull));
   __syncthreads();  // previous users of scratch are done
   if (lane == 0) scratch[wave] = __popcll(ball);
   __syncthreads();
   int off = 0, tot = 0;
 #pragma unroll
-  for (int w = 0; w < 4; ++w) {
+  for (int w = 0; w < kW; ++w) {
     int c = scratch[w];
     if (w < wave) off += c;
     tot += c;
@@ -122,7 +125,8 @@ __device__ __forceinline__ int block_excl_count(bool flag, int* scratch, int& to
   return off + before;
 }
 
-// Inclusive prefix sum over the 256 threads of a workgroup.  `scratch`: 4 ints of LDS.
+// Inclusive prefix sum over the threads of a workgroup of kW waves.  `scratch`: kW ints of LDS.
+template <int kW = 4>
 __device__ __forceinline__ int block_incl_scan(int v, int* scratch) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
@@ -135,7 +139,7 @@ __device__ __forceinline__ int block_incl_scan(int v, int* scratch) {
   __syncthreads();
   int add = 0;
 #pragma unroll
-  for (int w = 0; w < 4; ++w)
+  for (int w = 0; w < kW - 1; ++w)
     if (w < wave) add += scratch[w];
   return v + add;
 }

@@ -271,9 +271,9 @@ __device__ __forceinline__ double exact_score_wave(const uint16_t* __restrict__ 
 }
 
 // Most-significant-digit-first radix select over `n` keys read through `load(r)`: returns the k-th
-// largest key and how many of the keys equal to it belong to the top k.  256 threads; `hist` is
-// 256 ints of LDS, `scan_scratch` 4 ints, `s_pair` 2 ints.
-template <typename KeyT, typename Load>
+// largest key and how many of the keys equal to it belong to the top k.  Any multiple of 256 threads; `hist`
+// is 256 ints of LDS, `scan_scratch` one int per wave, `s_pair` 2 ints.
+template <typename KeyT, int kT, typename Load>
 __device__ __forceinline__ void radix_select(Load load, int n, int k, int* hist, int* scan_scratch, int* s_pair,
                                              KeyT& kth_out, int& krem_out) {
   constexpr int kPasses = sizeof(KeyT);
@@ -283,9 +283,9 @@ __device__ __forceinline__ void radix_select(Load load, int n, int k, int* hist,
   for (int pass = kPasses - 1; pass >= 0; --pass) {
     const int shift = pass * 8;
     const KeyT hi_mask = pass == kPasses - 1 ? (KeyT)0 : (KeyT)(~(KeyT)0 << (shift + 8));
-    hist[tid] = 0;
+    if (tid < 256) hist[tid] = 0;
     __syncthreads();
-    for (int base = 0; base < n; base += 256) {
+    for (int base = 0; base < n; base += kT) {
       const int r = base + tid;
       bool match = false;
       unsigned digit = 0;
@@ -309,11 +309,11 @@ __device__ __forceinline__ void radix_select(Load load, int n, int k, int* hist,
       }
     }
     __syncthreads();
-    const int dg = 255 - tid;  // thread t owns digit 255 - t: a prefix sum over threads is a suffix sum over digits
-    const int c = hist[dg];
-    const int incl = block_incl_scan(c, scan_scratch);
+    const int dg = 255 - tid;  // thread t < 256 owns digit 255 - t: a prefix sum over threads is a suffix sum over digits
+    const int c = tid < 256 ? hist[dg] : 0;
+    const int incl = block_incl_scan<kT / 64>(c, scan_scratch);
     const int excl = incl - c;
-    if (excl < krem && krem <= incl) {
+    if (tid < 256 && excl < krem && krem <= incl) {
       s_pair[0] = dg;
       s_pair[1] = krem - excl;
     }
@@ -329,13 +329,13 @@ __device__ __forceinline__ void radix_select(Load load, int n, int k, int* hist,
 // LDS of one top-k workgroup.
 struct TopkShared {
   int hist[256];
-  int scan[4];
-  int count_a[4];
-  int count_b[4];
+  int scan[kMaxWaves];
+  int count_a[kMaxWaves];
+  int count_b[kMaxWaves];
   int pair[2];
   int total;
-  float wmax[4];
-  uint32_t kmin[4], kmax[4];
+  float wmax[kMaxWaves];
+  uint32_t kmin[kMaxWaves], kmax[kMaxWaves];
   int amb_idx[kAmbCap];         // band candidates, ascending
   uint64_t amb_key[kAmbCap];    // their exact keys
   unsigned char amb_chosen[kAmbCap];
@@ -368,7 +368,7 @@ struct TopkArgs {
 
 // Fills the task of head blockIdx.x of sequence blockIdx.y, writes cnt, and finishes the two trivial
 // cases (nothing kept / everything kept) on the spot.  Returns false when the head is done.
-template <int kD>
+template <int kD, int kT>
 __device__ __forceinline__ bool begin_head(const Params& P, const TopkArgs& A, HeadTask& t) {
   const int b = blockIdx.y, h = blockIdx.x, j = h / P.group, tid = threadIdx.x;
   const Geo geo = geometry(P, b, j);
@@ -391,7 +391,7 @@ __device__ __forceinline__ bool begin_head(const Params& P, const TopkArgs& A, H
   t.keys64 = A.keys64 + slot * P.nb_stride + geo.n_sink;
   if (tid == 0) A.cnt[slot] = t.k;
   if (t.k == 0 || t.k == t.n) {
-    for (int r = tid; r < P.k_max; r += 256) t.out[r] = r < t.k ? t.n_sink + r : -1;
+    for (int r = tid; r < P.k_max; r += kT) t.out[r] = r < t.k ? t.n_sink + r : -1;
     return false;
   }
   return true;
@@ -399,6 +399,7 @@ __device__ __forceinline__ bool begin_head(const Params& P, const TopkArgs& A, H
 
 // 2 * gamma * (largest magnitude sum of the head): half-width of the band around the k-th approximate score.
 // `amax` is this thread's partial maximum over the head's tile magnitudes.
+template <int kT>
 __device__ __forceinline__ float band_half_width(float amax, TopkShared& sh) {
   const int tid = threadIdx.x;
 #pragma unroll
@@ -406,16 +407,19 @@ __device__ __forceinline__ float band_half_width(float amax, TopkShared& sh) {
   __syncthreads();
   if ((tid & 63) == 0) sh.wmax[tid >> 6] = amax;
   __syncthreads();
-  amax = fmaxf(fmaxf(sh.wmax[0], sh.wmax[1]), fmaxf(sh.wmax[2], sh.wmax[3]));
+  amax = sh.wmax[0];
+#pragma unroll
+  for (int w = 1; w < kT / 64; ++w) amax = fmaxf(amax, sh.wmax[w]);
   return 2.0f * kGamma * amax * 1.001f + 1e-30f;
 }
 
 // Exact path for a head whose band holds more candidates than LDS takes: exact fp64 scores for every
 // candidate, 64-bit radix select, ordered compaction (ties: lowest indices).
-template <int kD>
+template <int kD, int kT>
 __device__ __forceinline__ void exact_fallback(const Params& P, const HeadTask& t, TopkShared& sh) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  for (int r = wave; r < t.n; r += 4) {
+  constexpr int n_waves = kT / 64;
+  for (int r = wave; r < t.n; r += n_waves) {
     const double s = exact_score_wave<kD>(t.q_h, t.rows + (int64_t)r * 2 * kD, lane);
     if (lane == 0) t.keys64[r] = ordered_key64(s);
   }
@@ -423,31 +427,31 @@ __device__ __forceinline__ void exact_fallback(const Params& P, const HeadTask& 
   __syncthreads();
   uint64_t kth;
   int krem;
-  radix_select<uint64_t>([&](int r) { return t.keys64[r]; }, t.n, t.k, sh.hist, sh.scan, sh.pair, kth, krem);
+  radix_select<uint64_t, kT>([&](int r) { return t.keys64[r]; }, t.n, t.k, sh.hist, sh.scan, sh.pair, kth, krem);
   int run_sel = 0, run_eq = 0;
-  for (int base = 0; base < t.n; base += 256) {
+  for (int base = 0; base < t.n; base += kT) {
     const int r = base + tid;
     const uint64_t key = r < t.n ? t.keys64[r] : 0ull;
     const bool gt = r < t.n && key > kth;
     const bool eq = r < t.n && key == kth;
     int tot_eq, tot_sel;
-    const int eq_before = run_eq + block_excl_count(eq, sh.count_a, tot_eq);
+    const int eq_before = run_eq + block_excl_count<n_waves>(eq, sh.count_a, tot_eq);
     const bool sel = gt || (eq && eq_before < krem);
-    const int pos = run_sel + block_excl_count(sel, sh.count_b, tot_sel);
+    const int pos = run_sel + block_excl_count<n_waves>(sel, sh.count_b, tot_sel);
     if (sel && pos < P.k_max) t.out[pos] = t.n_sink + r;
     run_eq += tot_eq;
     run_sel += tot_sel;
   }
-  for (int r = t.k + tid; r < P.k_max; r += 256) t.out[r] = -1;
+  for (int r = t.k + tid; r < P.k_max; r += kT) t.out[r] = -1;
 }
 
 // Band candidates sh.amb_idx[0 .. n_amb) (ascending) -> sh.amb_chosen: the `need` best by (exact score
 // descending, index ascending).
-template <int kD>
+template <int kD, int kT>
 __device__ __forceinline__ void resolve_band(const HeadTask& t, TopkShared& sh, int n_amb, int need) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   __syncthreads();  // amb_idx is complete
-  for (int a = wave; a < n_amb; a += 4) {
+  for (int a = wave; a < n_amb; a += kT / 64) {
     const double s = exact_score_wave<kD>(t.q_h, t.rows + (int64_t)sh.amb_idx[a] * 2 * kD, lane);
     if (lane == 0) sh.amb_key[a] = ordered_key64(s);
   }
@@ -469,16 +473,16 @@ template <int kD>
 __global__ __launch_bounds__(256) void topk_kernel(Params P, TopkArgs A) {
   __shared__ TopkShared sh;
   HeadTask t;
-  if (!begin_head<kD>(P, A, t)) return;
+  if (!begin_head<kD, 256>(P, A, t)) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   auto ap = [&](int r) { return t.ap_base[(int64_t)(r >> 4) * t.tile_step + (r & 15)]; };
   float amax = 0.f;
   for (int r = tid; r < (t.n + 15) >> 4; r += 256) amax = fmaxf(amax, t.mag[r]);
-  const float eps2 = band_half_width(amax, sh);
+  const float eps2 = band_half_width<256>(amax, sh);
 
   uint32_t kth32;
   int krem32;
-  radix_select<uint32_t>([&](int r) { return ordered_key32(ap(r)); }, t.n, t.k, sh.hist, sh.scan, sh.pair, kth32,
+  radix_select<uint32_t, 256>([&](int r) { return ordered_key32(ap(r)); }, t.n, t.k, sh.hist, sh.scan, sh.pair, kth32,
                          krem32);
   const float T = key32_to_float(kth32);
   const float hi = T + eps2, lo = T - eps2;
@@ -506,7 +510,7 @@ __global__ __launch_bounds__(256) void topk_kernel(Params P, TopkArgs A) {
   const int need = t.k - n_sure;  // 1 <= need <= n_amb by construction of the band around the k-th key
 
   if (need < n_amb && n_amb > kAmbCap) {
-    exact_fallback<kD>(P, t, sh);
+    exact_fallback<kD, 256>(P, t, sh);
     return;
   }
   const bool resolve = need < n_amb;  // otherwise every band candidate is kept and no exact score is needed
@@ -521,7 +525,7 @@ __global__ __launch_bounds__(256) void topk_kernel(Params P, TopkArgs A) {
       if (amb) sh.amb_idx[pos] = r;
       run += tot;
     }
-    resolve_band<kD>(t, sh, n_amb, need);
+    resolve_band<kD, 256>(t, sh, n_amb, need);
   }
 
   // ordered compaction of the kept candidates
@@ -542,12 +546,14 @@ __global__ __launch_bounds__(256) void topk_kernel(Params P, TopkArgs A) {
   for (int r = t.k + tid; r < P.k_max; r += 256) t.out[r] = -1;
 }
 
-// Register-resident variant for n_cand <= 256 * KPT: thread t owns the KPT consecutive candidates
+// Register-resident variant for n_cand <= kT * KPT (kT threads): thread t owns the KPT consecutive candidates
 // t * KPT .. so that index order is thread order and every ordered compaction costs one block scan.
 // Keys are reduced to (key - smallest key) before the radix passes, which removes the sign/exponent
 // digits all candidates share: the select takes ceil(log2(span) / 8) passes, usually 3.
-template <int kD, int KPT>
-__global__ __launch_bounds__(256) void topk_reg_kernel(Params P, TopkArgs A) {
+template <int kD, int KPT, int kT>
+__global__ __launch_bounds__(kT) void topk_reg_kernel(Params P, TopkArgs A) {
+  constexpr int kW = kT / 64;                 // waves
+  constexpr int kMagPer = (512 + kT - 1) / kT;  // tile magnitudes per thread (at most 512 tiles)
   __shared__ TopkShared sh;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r0 = tid * KPT;
@@ -555,7 +561,7 @@ __global__ __launch_bounds__(256) void topk_reg_kernel(Params P, TopkArgs A) {
   // depend on the sequence length, so they travel together with the loads the geometry waits for instead
   // of after them.  Slots past the last candidate hold stale data and are masked below.
   float4 raw[KPT / 4];
-  float mag_raw[2];
+  float mag_raw[kMagPer];
   {
     const int h = blockIdx.x, j = h / P.group;
     const float* ap_base =
@@ -569,15 +575,15 @@ __global__ __launch_bounds__(256) void topk_reg_kernel(Params P, TopkArgs A) {
     }
     const float* mg = A.mag + ((int64_t)blockIdx.y * P.n_q_heads + h) * A.mag_stride;
 #pragma unroll
-    for (int u = 0; u < 2; ++u) mag_raw[u] = tid + u * 256 < A.mag_stride ? mg[tid + u * 256] : 0.f;  // <= 512 tiles
+    for (int u = 0; u < kMagPer; ++u) mag_raw[u] = tid + u * kT < A.mag_stride ? mg[tid + u * kT] : 0.f;
   }
   HeadTask t;
-  if (!begin_head<kD>(P, A, t)) return;
+  if (!begin_head<kD, kT>(P, A, t)) return;
   float amax = 0.f;
 #pragma unroll
-  for (int u = 0; u < 2; ++u)
-    if (tid + u * 256 < (t.n + 15) >> 4) amax = fmaxf(amax, mag_raw[u]);
-  const float eps2 = band_half_width(amax, sh);
+  for (int u = 0; u < kMagPer; ++u)
+    if (tid + u * kT < (t.n + 15) >> 4) amax = fmaxf(amax, mag_raw[u]);
+  const float eps2 = band_half_width<kT>(amax, sh);
 
   // keys of this thread's candidates (0 = no candidate: below every real key) and the key range
   uint32_t key[KPT];
@@ -605,8 +611,13 @@ __global__ __launch_bounds__(256) void topk_reg_kernel(Params P, TopkArgs A) {
     sh.kmax[wave] = kmax;
   }
   __syncthreads();
-  kmin = min(min(sh.kmin[0], sh.kmin[1]), min(sh.kmin[2], sh.kmin[3]));
-  kmax = max(max(sh.kmax[0], sh.kmax[1]), max(sh.kmax[2], sh.kmax[3]));
+  kmin = sh.kmin[0];
+  kmax = sh.kmax[0];
+#pragma unroll
+  for (int w = 1; w < kW; ++w) {
+    kmin = min(kmin, sh.kmin[w]);
+    kmax = max(kmax, sh.kmax[w]);
+  }
 
   // radix select of the k-th largest key on u = key - kmin, most significant digit first
   const uint32_t span = kmax - kmin;
@@ -616,7 +627,7 @@ __global__ __launch_bounds__(256) void topk_reg_kernel(Params P, TopkArgs A) {
   for (int pass = (n_bits + 7) / 8 - 1; pass >= 0; --pass) {
     const int shift = pass * 8;
     const uint32_t hi_mask = shift + 8 >= 32 ? 0u : (~0u << (shift + 8));
-    sh.hist[tid] = 0;
+    if (tid < 256) sh.hist[tid] = 0;
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < KPT; ++i) {
@@ -624,11 +635,11 @@ __global__ __launch_bounds__(256) void topk_reg_kernel(Params P, TopkArgs A) {
       if (key[i] != 0u && (u & hi_mask) == prefix) atomicAdd(&sh.hist[(u >> shift) & 255u], 1);
     }
     __syncthreads();
-    const int dg = 255 - tid;
-    const int c = sh.hist[dg];
-    const int incl = block_incl_scan(c, sh.scan);
+    const int dg = 255 - tid;  // threads 0..255 own one digit each
+    const int c = tid < 256 ? sh.hist[dg] : 0;
+    const int incl = block_incl_scan<kW>(c, sh.scan);
     const int excl = incl - c;
-    if (excl < krem && krem <= incl) {
+    if (tid < 256 && excl < krem && krem <= incl) {
       sh.pair[0] = dg;
       sh.pair[1] = krem - excl;
     }
@@ -647,19 +658,19 @@ __global__ __launch_bounds__(256) void topk_reg_kernel(Params P, TopkArgs A) {
     c_sure += key[i] > hi_key;
     c_amb += key[i] >= lo_key && key[i] <= hi_key;
   }
-  const int sure_incl = block_incl_scan(c_sure, sh.scan);
-  if (tid == 255) sh.total = sure_incl;
+  const int sure_incl = block_incl_scan<kW>(c_sure, sh.scan);
+  if (tid == kT - 1) sh.total = sure_incl;
   __syncthreads();
   const int n_sure = sh.total;
-  const int amb_incl = block_incl_scan(c_amb, sh.scan);
-  if (tid == 255) sh.total = amb_incl;
+  const int amb_incl = block_incl_scan<kW>(c_amb, sh.scan);
+  if (tid == kT - 1) sh.total = amb_incl;
   __syncthreads();
   const int n_amb = sh.total;
   const int amb_base = amb_incl - c_amb;
   const int need = t.k - n_sure;  // 1 <= need <= n_amb by construction of the band around the k-th key
 
   if (need < n_amb && n_amb > kAmbCap) {
-    exact_fallback<kD>(P, t, sh);
+    exact_fallback<kD, kT>(P, t, sh);
     return;
   }
   const bool resolve = need < n_amb;  // otherwise every band candidate is kept and no exact score is needed
@@ -668,7 +679,7 @@ __global__ __launch_bounds__(256) void topk_reg_kernel(Params P, TopkArgs A) {
 #pragma unroll
     for (int i = 0; i < KPT; ++i)
       if (key[i] >= lo_key && key[i] <= hi_key) sh.amb_idx[a++] = r0 + i;
-    resolve_band<kD>(t, sh, n_amb, need);
+    resolve_band<kD, kT>(t, sh, n_amb, need);
   }
 
   // ordered compaction of the kept candidates
@@ -687,14 +698,14 @@ __global__ __launch_bounds__(256) void topk_reg_kernel(Params P, TopkArgs A) {
       c_sel += sel;
     }
   }
-  int pos = block_incl_scan(c_sel, sh.scan) - c_sel;
+  int pos = block_incl_scan<kW>(c_sel, sh.scan) - c_sel;
 #pragma unroll
   for (int i = 0; i < KPT; ++i)
     if ((sel_bits >> i) & 1u) {
       if (pos < P.k_max) t.out[pos] = t.n_sink + r0 + i;
       ++pos;
     }
-  for (int r = t.k + tid; r < P.k_max; r += 256) t.out[r] = -1;
+  for (int r = t.k + tid; r < P.k_max; r += kT) t.out[r] = -1;
 }
 
 float select_error_gamma() { return kGamma; }
@@ -749,18 +760,29 @@ hipError_t launch_select(const Params& P, const void* q, const void* S, const fl
   const dim3 tgrid(P.n_q_heads, P.batch);
   const TopkArgs A{(const uint16_t*)q, (const uint16_t*)S, approx, mag, keys, budget_frac, budget_blocks, idx, cnt,
                    mag_stride};
-#define FX_TOPK_REG(D, KPT) hipLaunchKernelGGL((topk_reg_kernel<D, KPT>), tgrid, dim3(256), 0, stream, P, A)
+  // keys per thread x threads per head: 4 x 256 for up to 1024 blocks, then wider workgroups before longer
+  // per-thread key lists (every phase of the kernel is a chain of barriers and per-thread loops over the keys)
+#ifndef FX_TOPK_T2
+#define FX_TOPK_T2 256   // threads up to 2048 blocks (512 measured no better)
+#endif
+#ifndef FX_TOPK_T4
+#define FX_TOPK_T4 512   // threads up to 4096 blocks (256: +1.4 us, 1024: +9 us at 512 heads)
+#endif
+#ifndef FX_TOPK_T8
+#define FX_TOPK_T8 1024  // threads up to 8192 blocks (256: +4.5 us, 512: +0.6 us)
+#endif
+#define FX_TOPK_REG(D, KPT, T) hipLaunchKernelGGL((topk_reg_kernel<D, KPT, T>), tgrid, dim3(T), 0, stream, P, A)
   if (P.head_dim == 128) {
-    if (P.nb_stride <= 1024) FX_TOPK_REG(128, 4);
-    else if (P.nb_stride <= 2048) FX_TOPK_REG(128, 8);
-    else if (P.nb_stride <= 4096) FX_TOPK_REG(128, 16);
-    else if (P.nb_stride <= 8192) FX_TOPK_REG(128, 32);
+    if (P.nb_stride <= 1024) FX_TOPK_REG(128, 4, 256);
+    else if (P.nb_stride <= 2048) FX_TOPK_REG(128, 2048 / FX_TOPK_T2, FX_TOPK_T2);
+    else if (P.nb_stride <= 4096) FX_TOPK_REG(128, 4096 / FX_TOPK_T4, FX_TOPK_T4);
+    else if (P.nb_stride <= 8192) FX_TOPK_REG(128, 8192 / FX_TOPK_T8, FX_TOPK_T8);
     else hipLaunchKernelGGL(topk_kernel<128>, tgrid, dim3(256), 0, stream, P, A);
   } else {
-    if (P.nb_stride <= 1024) FX_TOPK_REG(64, 4);
-    else if (P.nb_stride <= 2048) FX_TOPK_REG(64, 8);
-    else if (P.nb_stride <= 4096) FX_TOPK_REG(64, 16);
-    else if (P.nb_stride <= 8192) FX_TOPK_REG(64, 32);
+    if (P.nb_stride <= 1024) FX_TOPK_REG(64, 4, 256);
+    else if (P.nb_stride <= 2048) FX_TOPK_REG(64, 2048 / FX_TOPK_T2, FX_TOPK_T2);
+    else if (P.nb_stride <= 4096) FX_TOPK_REG(64, 4096 / FX_TOPK_T4, FX_TOPK_T4);
+    else if (P.nb_stride <= 8192) FX_TOPK_REG(64, 8192 / FX_TOPK_T8, FX_TOPK_T8);
     else hipLaunchKernelGGL(topk_kernel<64>, tgrid, dim3(256), 0, stream, P, A);
   }
 #undef FX_TOPK_REG
