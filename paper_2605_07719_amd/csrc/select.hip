@@ -341,6 +341,20 @@ struct TopkShared {
   unsigned char amb_chosen[kAmbCap];
 };
 
+// out[from .. to) = -1 (the padding behind a head's index list), 16 bytes per store where alignment allows.
+template <int kT>
+__device__ __forceinline__ void pad_minus_one(int32_t* out, int from, int to) {
+  const int tid = threadIdx.x;
+  const int shift = (int)((reinterpret_cast<uintptr_t>(out) >> 2) & 3);  // elements past a 16-byte boundary
+  int lo = ((from + shift + 3) & ~3) - shift;                            // first index whose address is aligned
+  lo = lo < to ? lo : to;
+  const int n_vec = (to - lo) >> 2;
+  for (int r = from + tid; r < lo; r += kT) out[r] = -1;
+  int4* v = reinterpret_cast<int4*>(out + lo);
+  for (int x = tid; x < n_vec; x += kT) v[x] = make_int4(-1, -1, -1, -1);
+  for (int r = lo + 4 * n_vec + tid; r < to; r += kT) out[r] = -1;
+}
+
 // Everything the top-k of one (sequence, query head) needs.
 struct HeadTask {
   int k, n, n_sink;           // blocks to keep, candidates, index of the first candidate block
@@ -442,7 +456,7 @@ __device__ __forceinline__ void exact_fallback(const Params& P, const HeadTask& 
     run_eq += tot_eq;
     run_sel += tot_sel;
   }
-  for (int r = t.k + tid; r < P.k_max; r += kT) t.out[r] = -1;
+  pad_minus_one<kT>(t.out, t.k, P.k_max);
 }
 
 // Band candidates sh.amb_idx[0 .. n_amb) (ascending) -> sh.amb_chosen: the `need` best by (exact score
@@ -543,7 +557,7 @@ __global__ __launch_bounds__(256) void topk_kernel(Params P, TopkArgs A) {
     run_amb += tot_amb;
     run_sel += tot_sel;
   }
-  for (int r = t.k + tid; r < P.k_max; r += 256) t.out[r] = -1;
+  pad_minus_one<256>(t.out, t.k, P.k_max);
 }
 
 // Register-resident variant for n_cand <= kT * KPT (kT threads): thread t owns the KPT consecutive candidates
@@ -705,7 +719,7 @@ __global__ __launch_bounds__(kT) void topk_reg_kernel(Params P, TopkArgs A) {
       if (pos < P.k_max) t.out[pos] = t.n_sink + r0 + i;
       ++pos;
     }
-  for (int r = t.k + tid; r < P.k_max; r += kT) t.out[r] = -1;
+  pad_minus_one<kT>(t.out, t.k, P.k_max);
 }
 
 float select_error_gamma() { return kGamma; }
