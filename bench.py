@@ -230,8 +230,8 @@ def stream_probe(n_bytes=4 << 30) -> dict:
         torch.cuda.synchronize()
         return ev0.elapsed_time(ev1) / reps
 
-    read = {w: n_bytes / timed(lambda: F.probe_read(src, sink, w)) / 1e6 for w in (1, 2, 8)}
-    read_nt = {w: n_bytes / timed(lambda: F.probe_read_streaming(src, sink, w)) / 1e6 for w in (1, 2, 8)}
+    read = {w: n_bytes / timed(lambda: F.probe_read(src, sink, w)) / 1e6 for w in (1, 2, 3)}
+    read_nt = {w: n_bytes / timed(lambda: F.probe_read_streaming(src, sink, w)) / 1e6 for w in (1, 2, 3)}
     copy_ms = timed(lambda: F.probe_copy(dst, src, 4))
     return {"bytes": n_bytes, "read_GBps": max(max(read.values()), max(read_nt.values())),
             "plain_read_GBps_by_wg_per_cu": read, "non_temporal_read_GBps_by_wg_per_cu": read_nt,
