@@ -12,8 +12,10 @@
 //                  sequence; every workgroup of the launch takes an equal contiguous share of it (a
 //                  "unit"), so the work per workgroup is balanced whatever the budgets, block sizes
 //                  and sequence lengths are.  Where a unit crosses from one group into the next it
-//                  is cut into segments.  Within a segment each wave takes every fourth slice:
-//                  coalesced 16-byte-per-lane loads of K and V rows, fp32 dot products reduced inside
+//                  is cut into segments; the tail of the sequence is cut into small units that
+//                  workgroups claim from a counter as they finish.  Within a segment each wave takes
+//                  every fourth slice: coalesced, non-temporal 16-byte-per-lane loads of K and V rows
+//                  (each row is read once per step), fp32 dot products reduced inside
 //                  the 8/16 lanes that share a token, running (max, sum, accumulator) per head in
 //                  registers.  Per segment one partial triple per head is written, to slot
 //                  unit + group (strictly increasing along the slice sequence, hence unique).
@@ -139,7 +141,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Params P, const int3
 
 // Division of the global slice sequence into units (a slice is 16 tokens of a union list).
 //
-// Throughput regime (at least kMinShare slices per workgroup): the first `n_static` units, one per
+// Throughput regime (at least FX_MIN_SHARE slices per workgroup): the first `n_static` units, one per
 // workgroup of the launch and taken by workgroup number, are equal shares of the leading part of the
 // sequence; the rest is cut into small units that workgroups claim from a counter as they become free.
 // The claimed part evens out the differences in speed between workgroups (equal shares finish up to
@@ -392,10 +394,10 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
       } else {
         // logits (log2 domain) of the slice's tokens for every head that wants this block
         float sp[kG][kLoads];
-  #pragma unroll
+#pragma unroll
         for (int i = 0; i < kLoads; ++i) {
           const bool valid = t0 + i * kTPL < geo.n_tokens;
-  #pragma unroll
+#pragma unroll
           for (int r = 0; r < kG; ++r) {
             if (mask & (1u << r)) {
               float dot = dot2_bf16(qp[r].x, kraw[i].x, 0.f);
@@ -408,16 +410,16 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
           }
         }
         // online-softmax update per head: new maximum, rescale, probabilities
-  #pragma unroll
+#pragma unroll
         for (int r = 0; r < kG; ++r) {
           if (mask & (1u << r)) {
             float mx = sp[r][0];
-  #pragma unroll
+#pragma unroll
             for (int i = 1; i < kLoads; ++i) mx = fmaxf(mx, sp[r][i]);
             const float m_new = fmaxf(m_run[r], mx);
             const float alpha = __builtin_amdgcn_exp2f(m_run[r] - m_new);
             float psum = 0.f;
-  #pragma unroll
+#pragma unroll
             for (int i = 0; i < kLoads; ++i) {
               const bool valid = t0 + i * kTPL < geo.n_tokens;
               sp[r][i] = valid ? __builtin_amdgcn_exp2f(sp[r][i] - m_new) : 0.f;
@@ -426,20 +428,20 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
             l_run[r] = l_run[r] * alpha + psum;
             m_run[r] = m_new;
             if (__ballot(alpha != 1.f)) {  // the maximum moved somewhere in the wave (rare once warmed up)
-  #pragma unroll
+#pragma unroll
               for (int c = 0; c < 8; ++c) acc[r][c] *= alpha;
             }
           }
         }
         // acc += p * v
-  #pragma unroll
+#pragma unroll
         for (int i = 0; i < kLoads; ++i) {
           float vf[8];
           unpack8(vraw[i], vf);
-  #pragma unroll
+#pragma unroll
           for (int r = 0; r < kG; ++r) {
             if (mask & (1u << r)) {
-  #pragma unroll
+#pragma unroll
               for (int c = 0; c < 8; ++c) acc[r][c] = fmaf(sp[r][i], vf[c], acc[r][c]);
             }
           }

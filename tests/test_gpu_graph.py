@@ -11,8 +11,7 @@ from test_gpu_parity import TOL, run_oracle, small_cases
 pytestmark = pytest.mark.gpu
 
 
-def test_graph_replays_match_eager_and_oracle():
-    wl = small_cases()["d128_g4"]
+def _graph_case(wl):
     layers = [W.make_layer(wl, layer) for layer in range(3)]
     refs = [run_oracle(wl, t) for t in layers]
     gps = [GpuProblem(wl, t, k_max=refs[0]["k_max"]) for t in layers]
@@ -63,3 +62,31 @@ def test_graph_replays_match_eager_and_oracle():
         step(rep % 3)                                  # an eager step between replays
         torch.cuda.synchronize()
         assert torch.equal(outs[rep % 3], eager[rep % 3])
+
+
+def test_graph_replays_match_eager_and_oracle():
+    _graph_case(small_cases()["d128_g4"])
+
+
+def test_graph_replays_with_claimed_units():
+    """A step large enough for the attention kernel's throughput regime (static shares plus units claimed from
+    a counter that the plan kernel resets): replays must still reproduce the eager bits."""
+    B = 8
+    wl = W.Workload(name="graph_claimed", n_q_heads=8, n_kv_heads=4, head_dim=64, seq_len=[32768] * B,
+                    gran=[16, 32, 16, 32], sink_tokens=64, window_tokens=256,
+                    budget_frac=np.full((B, 8), 0.9, dtype=np.float32), seed=21)
+    _graph_case(wl)
+
+
+def test_stream_probes_run():
+    """The measurement aids (plain read, non-temporal read, copy) accept a device buffer and complete."""
+    from paper_2605_07719_amd import fluxion as F
+
+    src = torch.arange(1 << 20, dtype=torch.int32, device="cuda")
+    dst = torch.zeros_like(src)
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    F.probe_read(src, sink, 2)
+    F.probe_read_streaming(src, sink, 2)
+    F.probe_copy(dst, src, 2)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
