@@ -109,7 +109,8 @@ size_t fx_select_workspace_bytes(const fx_layout* layout);
  *   idx            int32 [batch][n_q_heads][k_max], written: the kept block indices in ascending
  *                  order, then -1 up to k_max
  *   cnt            int32 [batch][n_q_heads], written: k_h
- *   workspace      >= fx_select_workspace_bytes(layout) bytes, 16-byte aligned; contents undefined after
+ *   workspace      >= fx_select_workspace_bytes(layout) bytes, 16-byte aligned; contents undefined after;
+ *                  calls that may overlap in time (different streams) need a workspace each
  * A budget of 0 keeps nothing (streaming head: only sink and window are attended, Sec. 3.2); a budget
  * of 1.0 keeps every candidate, which makes the later attention dense.
  * Errors: INVALID_ARG (null/misaligned, both or neither budget, k_max < 1, negative sink/window),
@@ -148,7 +149,8 @@ size_t fx_decode_workspace_bytes(const fx_layout* layout, int32_t k_max, int32_t
  *              [0, n_blocks) are ignored, duplicates and entries inside sink/window are harmless,
  *              cnt is clamped to [0, k_max]
  *   out        float [batch][n_q_heads][head_dim], written (zeros for a sequence of length 0)
- *   workspace  >= fx_decode_workspace_bytes(...) bytes, 16-byte aligned; contents undefined after
+ *   workspace  >= fx_decode_workspace_bytes(...) bytes, 16-byte aligned; contents undefined after;
+ *              calls that may overlap in time (different streams) need a workspace each
  * Arithmetic: bf16 inputs, fp32 products, sums, exponentials and accumulators.
  * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP. */
 fx_status fx_sparse_decode(const fx_layout* layout, const void* q, const void* K, const void* V, const int32_t* idx,
