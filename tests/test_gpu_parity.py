@@ -388,5 +388,7 @@ def test_work_split_units_span_several_groups():
     wl = W.Workload(name="split_span", n_q_heads=8, n_kv_heads=4, head_dim=64,
                     seq_len=[int(x) for x in rng.integers(300, 700, size=B)], gran=[16, 32, 16, 48], sink_tokens=16,
                     window_tokens=64, budget_frac=np.full((B, 8), 1.0, dtype=np.float32), seed=12)
+    wl.budget_frac[::2, 2:4] = 0.0   # every other sequence: KV head 1 is a group of streaming heads (no scores)
+    wl.budget_frac[1::3, 6] = 0.25   # and some sparse heads next to dense ones
     print(f"case=split_span B={B}", flush=True)
     _split_case(wl)
