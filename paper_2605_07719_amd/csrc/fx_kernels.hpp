@@ -66,15 +66,15 @@ inline DecodeWorkspace carve_decode(const Params& P) {
     if (u > ucap) ucap = u;
   }
   if (ucap < 1) ucap = 1;
-  const int64_t items = (int64_t)kMaxUnits * (1 + kClaimedPerWg) + 2 * n_groups + 8;
+  const int64_t slots = (int64_t)kMaxUnits * (1 + kClaimedPerWg) + 2 * n_groups + 8;
   W.union_cap = (int32_t)ucap;
-  W.slots_cap = (int32_t)items;
+  W.slots_cap = (int32_t)slots;
   size_t off = 0;
   W.union_off = off;  off += align_up((size_t)n_groups * ucap * sizeof(uint32_t));
   W.ucount_off = off; off += align_up((size_t)n_groups * sizeof(int32_t));
   W.sched_off = off;  off += align_up((size_t)(n_groups + 8) * sizeof(int32_t));
-  W.acc_off = off;    off += align_up((size_t)items * P.group * P.head_dim * sizeof(float));
-  W.ml_off = off;     off += align_up((size_t)items * P.group * 2 * sizeof(float));
+  W.acc_off = off;    off += align_up((size_t)slots * P.group * P.head_dim * sizeof(float));
+  W.ml_off = off;     off += align_up((size_t)slots * P.group * 2 * sizeof(float));
   W.total = off;
   return W;
 }

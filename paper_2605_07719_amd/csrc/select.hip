@@ -7,10 +7,10 @@
 // i.e. one row of a dense product  [q- | q+] (G x 2d)  times  [mn | mx]^T (2d x n_cand): the summary
 // rows are stored exactly as [mn | mx], so the stream of summaries feeds the matrix cores directly.
 //
-// Stage 1 (score_kernel): per (sequence, KV head) stream the candidate summaries once; bf16 MFMA
+// Stage 1 (score_grid_kernel / score_stream_kernel): per (sequence, KV head) stream the candidate summaries once; bf16 MFMA
 //   (16x16x32, fp32 accumulate) gives, for all heads of the group at once, an approximate score
 //   s~ and the magnitude sum a~ = sum_c (|q-_c| |mn_c| + |q+_c| |mx_c|) that bounds its rounding error.
-// Stage 2 (topk_kernel): per (sequence, query head) a radix select on the fp32 keys finds the k-th
+// Stage 2 (topk_reg_kernel / topk_kernel): per (sequence, query head) a radix select on the fp32 keys finds the k-th
 //   largest s~ = T.  With eps = gamma * max a~, every candidate above T + 2 eps is certainly among
 //   the exact top-k and every candidate below T - 2 eps certainly is not.  Only the few candidates
 //   inside the band are re-scored exactly (exact products, fp64 accumulation) and ranked by
