@@ -39,6 +39,9 @@ def small_cases():
             name="f", n_q_heads=2, n_kv_heads=1, head_dim=64, seq_len=[140000, 20000], gran=[16],
             sink_tokens=64, window_tokens=256, budget_frac=np.array([[0.03, 0.2], [0.5, 0.01]], dtype=np.float32),
             seed=6),
+        "max_context_2e19": W.Workload(
+            name="g", n_q_heads=2, n_kv_heads=1, head_dim=64, seq_len=[524288], gran=[16],
+            sink_tokens=64, window_tokens=256, budget_frac=np.array([[0.02, 0.001]], dtype=np.float32), seed=7),
         "mha_g1": W.Workload(
             name="e", n_q_heads=3, n_kv_heads=3, head_dim=128, seq_len=[1500, 900], gran=[16, 32, 80],
             sink_tokens=64, window_tokens=256, budget_frac=np.full((2, 3), 0.15, dtype=np.float32), seed=5),
