@@ -413,6 +413,8 @@ __device__ __forceinline__ bool begin_head(const Params& P, const TopkArgs& A, H
 
 // 2 * gamma * (largest magnitude sum of the head): half-width of the band around the k-th approximate score.
 // `amax` is this thread's partial maximum over the head's tile magnitudes.
+__device__ __forceinline__ float band_width_from_max(float amax) { return 2.0f * kGamma * amax * 1.001f + 1e-30f; }
+
 template <int kT>
 __device__ __forceinline__ float band_half_width(float amax, TopkShared& sh) {
   const int tid = threadIdx.x;
@@ -424,7 +426,7 @@ __device__ __forceinline__ float band_half_width(float amax, TopkShared& sh) {
   amax = sh.wmax[0];
 #pragma unroll
   for (int w = 1; w < kT / 64; ++w) amax = fmaxf(amax, sh.wmax[w]);
-  return 2.0f * kGamma * amax * 1.001f + 1e-30f;
+  return band_width_from_max(amax);
 }
 
 // Exact path for a head whose band holds more candidates than LDS takes: exact fp64 scores for every
@@ -597,9 +599,8 @@ __global__ __launch_bounds__(kT) void topk_reg_kernel(Params P, TopkArgs A) {
 #pragma unroll
   for (int u = 0; u < kMagPer; ++u)
     if (tid + u * kT < (t.n + 15) >> 4) amax = fmaxf(amax, mag_raw[u]);
-  const float eps2 = band_half_width<kT>(amax, sh);
-
-  // keys of this thread's candidates (0 = no candidate: below every real key) and the key range
+  // keys of this thread's candidates (0 = no candidate: below every real key) and the key range; the
+  // largest magnitude, the smallest and the largest key are reduced together behind one barrier
   uint32_t key[KPT];
   uint32_t kmin = 0xffffffffu, kmax = 0u;
 #pragma unroll
@@ -619,19 +620,25 @@ __global__ __launch_bounds__(kT) void topk_reg_kernel(Params P, TopkArgs A) {
   for (int off = 1; off < 64; off <<= 1) {
     kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, off, kWave));
     kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, off, kWave));
+    amax = fmaxf(amax, __shfl_xor(amax, off, kWave));
   }
   if (lane == 0) {
     sh.kmin[wave] = kmin;
     sh.kmax[wave] = kmax;
+    sh.wmax[wave] = amax;
   }
+  if (tid < 256) sh.hist[tid] = 0;  // for the first radix pass
   __syncthreads();
   kmin = sh.kmin[0];
   kmax = sh.kmax[0];
+  amax = sh.wmax[0];
 #pragma unroll
   for (int w = 1; w < kW; ++w) {
     kmin = min(kmin, sh.kmin[w]);
     kmax = max(kmax, sh.kmax[w]);
+    amax = fmaxf(amax, sh.wmax[w]);
   }
+  const float eps2 = band_width_from_max(amax);
 
   // radix select of the k-th largest key on u = key - kmin, most significant digit first
   const uint32_t span = kmax - kmin;
@@ -641,8 +648,8 @@ __global__ __launch_bounds__(kT) void topk_reg_kernel(Params P, TopkArgs A) {
   for (int pass = (n_bits + 7) / 8 - 1; pass >= 0; --pass) {
     const int shift = pass * 8;
     const uint32_t hi_mask = shift + 8 >= 32 ? 0u : (~0u << (shift + 8));
-    if (tid < 256) sh.hist[tid] = 0;
-    __syncthreads();
+    // four barriers per pass: the histogram is empty on entry (its owner clears each bin right after reading
+    // it), and `pair` is not rewritten before three barriers of the next pass have passed
 #pragma unroll
     for (int i = 0; i < KPT; ++i) {
       const uint32_t u = key[i] - kmin;
@@ -650,7 +657,11 @@ __global__ __launch_bounds__(kT) void topk_reg_kernel(Params P, TopkArgs A) {
     }
     __syncthreads();
     const int dg = 255 - tid;  // threads 0..255 own one digit each
-    const int c = tid < 256 ? sh.hist[dg] : 0;
+    int c = 0;
+    if (tid < 256) {
+      c = sh.hist[dg];
+      sh.hist[dg] = 0;
+    }
     const int incl = block_incl_scan<kW>(c, sh.scan);
     const int excl = incl - c;
     if (tid < 256 && excl < krem && krem <= incl) {
@@ -660,7 +671,6 @@ __global__ __launch_bounds__(kT) void topk_reg_kernel(Params P, TopkArgs A) {
     __syncthreads();
     prefix |= (uint32_t)sh.pair[0] << shift;
     krem = sh.pair[1];
-    __syncthreads();
   }
   const float T = key32_to_float(kmin + prefix);
   const uint32_t hi_key = ordered_key32(T + eps2), lo_key = ordered_key32(T - eps2);
@@ -672,15 +682,12 @@ __global__ __launch_bounds__(kT) void topk_reg_kernel(Params P, TopkArgs A) {
     c_sure += key[i] > hi_key;
     c_amb += key[i] >= lo_key && key[i] <= hi_key;
   }
-  const int sure_incl = block_incl_scan<kW>(c_sure, sh.scan);
-  if (tid == kT - 1) sh.total = sure_incl;
+  // both counts in one scan: low half = certainly kept, high half = band (each at most 8192: no carry)
+  const int packed_incl = block_incl_scan<kW>(c_sure | (c_amb << 16), sh.scan);
+  if (tid == kT - 1) sh.total = packed_incl;
   __syncthreads();
-  const int n_sure = sh.total;
-  const int amb_incl = block_incl_scan<kW>(c_amb, sh.scan);
-  if (tid == kT - 1) sh.total = amb_incl;
-  __syncthreads();
-  const int n_amb = sh.total;
-  const int amb_base = amb_incl - c_amb;
+  const int n_sure = sh.total & 0xffff, n_amb = sh.total >> 16;
+  const int amb_base = (packed_incl >> 16) - c_amb;
   const int need = t.k - n_sure;  // 1 <= need <= n_amb by construction of the band around the k-th key
 
   if (need < n_amb && n_amb > kAmbCap) {
