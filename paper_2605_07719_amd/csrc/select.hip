@@ -165,11 +165,13 @@ __global__ __launch_bounds__(256) void score_grid_kernel(Params P, const uint16_
                                                          const int32_t* __restrict__ budget_blocks, int mag_stride) {
   const int b = blockIdx.z, j = blockIdx.y;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // budgets, summary offset and sequence length are requested together (one round trip, not three)
+  const bool any = group_selects(P, budget_frac, budget_blocks, b, j);
+  const int64_t first_block = P.sum_base[(int64_t)b * P.n_kv_heads + j];
   const Geo geo = geometry(P, b, j);
   const int tile = blockIdx.x * 4 + wave;
-  if (tile * 16 >= geo.n_cand) return;  // whole wave leaves
-  if (!group_selects(P, budget_frac, budget_blocks, b, j)) return;
-  const uint16_t* rows = S + (P.sum_base[(int64_t)b * P.n_kv_heads + j] + geo.n_sink) * (int64_t)(2 * kD);
+  if (tile * 16 >= geo.n_cand || !any) return;  // whole wave leaves
+  const uint16_t* rows = S + (first_block + geo.n_sink) * (int64_t)(2 * kD);
   score_tiles<kD>(P, q, rows, geo.n_cand, b, j, tile, tile + 1, approx, mag_tile, mag_stride, lane);
 }
 
