@@ -269,6 +269,68 @@ def output_deviation(ls: LayerSet) -> dict:
     return res
 
 
+def next_rows(ls: LayerSet, steps: int = 16) -> dict:
+    """Timings of the widened entry points on the workload of `ls`: group-union attention, the summary pyramid,
+    incremental summaries and the host-side granularity/budget selector."""
+    import torch
+
+    from paper_2605_07719_amd import fluxion as F
+    from paper_2605_07719_amd import traffic as T
+    from paper_2605_07719_amd import workloads as W
+
+    wl, pl = ls.wl, ls.pl
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(fn, reps=steps):
+        fn(0)
+        torch.cuda.synchronize()
+        ev0.record()
+        for i in range(reps):
+            fn(i)
+        ev1.record()
+        torch.cuda.synchronize()
+        return ev0.elapsed_time(ev1) / reps * 1e3  # us
+
+    out = {"workload": wl.name}
+    # group-union attention on the selections of fx_select (every head of a group attends over the union)
+    def union_step(i):
+        q, K, V, S = ls.layers[i % len(ls.layers)]
+        F.select(ls.layout, q, S, budget_frac=ls.bf, budget_blocks=ls.bb, sink_tokens=wl.sink_tokens,
+                 window_tokens=wl.window_tokens, k_max=ls.k_max, idx=ls.idx, cnt=ls.cnt, workspace=ls.ws_sel)
+        F.sparse_decode(ls.layout, q, K, V, ls.idx, ls.cnt, k_max=ls.k_max, sink_tokens=wl.sink_tokens,
+                        window_tokens=wl.window_tokens, out=ls.out, workspace=ls.ws_dec, group_union=True)
+    out["union_us_per_layer_step"] = timed(union_step)
+
+    # summary pyramid: coarse summaries at 4x the block size from the resident ones
+    if all(int(g) * 4 <= 128 for g in pl.gran):
+        wl_c = W.Workload(**{**wl.__dict__, "gran": [int(g) * 4 for g in pl.gran]})
+        pl_c = W.placement(wl_c)
+        lay_c = F.Layout.from_host(wl.n_q_heads, wl.n_kv_heads, wl.head_dim, pl_c.seq_len, pl_c.seq_base,
+                                   pl_c.kv_head_stride, pl_c.token_stride, pl_c.sum_base.reshape(-1), pl_c.gran,
+                                   device="cuda")
+        S_c = torch.empty((pl_c.total_blocks, 2, wl.head_dim), dtype=torch.bfloat16, device="cuda")
+        us = timed(lambda i: F.coarsen_summaries(ls.layout, ls.layers[i % len(ls.layers)][3], lay_c, S_c))
+        fine_bytes = pl.total_blocks * 2 * wl.head_dim * 2
+        out["coarsen_x4_us"] = us
+        out["coarsen_x4_GBps_on_fine_summaries"] = fine_bytes / (us * 1e-6) / 1e9
+
+    # incremental summaries: one new token per sequence (the block holding it is re-summarised)
+    prev = torch.from_numpy(np.maximum(np.asarray(pl.seq_len, dtype=np.int32) - 1, 0)).cuda()
+    out["summarize_append_1_token_us"] = timed(
+        lambda i: F.summarize_append(ls.layout, ls.layers[i % len(ls.layers)][1], ls.layers[i % len(ls.layers)][3],
+                                     prev, 1))
+
+    # host selector: Eq. 1 per head, Eq. 3 argmin per group
+    rng = np.random.default_rng(0)
+    bgt0 = rng.uniform(0.01, 0.2, wl.n_q_heads).astype(np.float32)
+    slope = rng.uniform(0.0, 0.02, wl.n_q_heads).astype(np.float32)
+    t0 = time.perf_counter()
+    for _ in range(200):
+        F.choose_granularity(wl.n_q_heads, wl.n_kv_heads, bgt0, slope, int(max(pl.seq_len)))
+    out["choose_granularity_host_us"] = (time.perf_counter() - t0) / 200 * 1e6
+    return out
+
+
 def cpu_baseline(wl, seconds=12.0) -> dict:
     """The oracle, as it stands, on this machine's host cores: selection + sparse attention of one layer-step."""
     import torch
@@ -348,6 +410,7 @@ def main():
     log("[bench] headline:", json.dumps(head))
 
     others = []
+    nxt = None
     if not args.no_extra and not args.only:
         for name, mk in extras.items():
             wl, nl = mk()
@@ -355,6 +418,9 @@ def main():
             r = measure(ls, max(8, args.steps // 4), max(4, args.warmup // 4), use_graph)
             log(f"[bench] {name}:", json.dumps(r))
             others.append(r)
+            if name == "hbm_stress":
+                nxt = next_rows(ls)
+                log("[bench] widened entry points:", json.dumps(nxt))
             del ls
             torch.cuda.empty_cache()
 
@@ -406,6 +472,7 @@ def main():
             "bytes_per_launch": others[0]["decode_unique_bytes"], "us_per_launch": others[0]["kernel_us"]["attend"],
         },
         "stream_probe": probe,
+        "next_rows": nxt,
         "workloads": others,
         "cpu_baseline": base,
     }
