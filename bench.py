@@ -299,7 +299,18 @@ def next_rows(ls: LayerSet, steps: int = 16) -> dict:
                  window_tokens=wl.window_tokens, k_max=ls.k_max, idx=ls.idx, cnt=ls.cnt, workspace=ls.ws_sel)
         F.sparse_decode(ls.layout, q, K, V, ls.idx, ls.cnt, k_max=ls.k_max, sink_tokens=wl.sink_tokens,
                         window_tokens=wl.window_tokens, out=ls.out, workspace=ls.ws_dec, group_union=True)
-    out["union_us_per_layer_step"] = timed(union_step)
+    for i in range(4):
+        union_step(i)
+    torch.cuda.synchronize()
+    F.profile_enable(True)
+    acc = {k: 0.0 for k in F.PROFILE_SLOTS}
+    for i in range(steps):
+        union_step(i)
+        for k, v in F.profile_read().items():
+            acc[k] += v / steps * 1e3
+    F.profile_enable(False)
+    out["union_kernel_us"] = acc                      # HIP events around each kernel, as in measure()
+    out["union_us_per_layer_step"] = sum(acc.values())
 
     # summary pyramid: coarse summaries at 4x the block size from the resident ones
     if all(int(g) * 4 <= 128 for g in pl.gran):
