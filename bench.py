@@ -299,7 +299,7 @@ def next_rows(ls: LayerSet, steps: int = 16) -> dict:
                  window_tokens=wl.window_tokens, k_max=ls.k_max, idx=ls.idx, cnt=ls.cnt, workspace=ls.ws_sel)
         F.sparse_decode(ls.layout, q, K, V, ls.idx, ls.cnt, k_max=ls.k_max, sink_tokens=wl.sink_tokens,
                         window_tokens=wl.window_tokens, out=ls.out, workspace=ls.ws_dec, group_union=True)
-    for i in range(4):
+    for i in range(64):  # the GPU idled while the host counted bytes: let the clocks come back up
         union_step(i)
     torch.cuda.synchronize()
     F.profile_enable(True)
