@@ -37,7 +37,7 @@ __global__ __launch_bounds__(256) void summarize_kernel(Params P, const uint16_t
 #pragma unroll
     for (int c = 0; c < 8; ++c) mx[c] = mn[c];
   }
-#pragma unroll 4
+#pragma unroll 8
   for (int t = t_lo + 1; t < t_hi; ++t) {
     uint4 r = stream_load16(src + (int64_t)t * P.token_stride);
     float x[8];
