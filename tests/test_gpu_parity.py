@@ -395,3 +395,34 @@ def test_work_split_units_span_several_groups():
     wl.budget_frac[1::3, 6] = 0.25   # and some sparse heads next to dense ones
     print(f"case=split_span B={B}", flush=True)
     _split_case(wl)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_medium_shapes_sweep(seed):
+    """Random problems of 30K-200K tokens: large enough for the stream score kernel and for the attention
+    kernel's static shares plus claimed units; group sizes 1..8, block sizes incl. 48, budgets incl. 0 and 1."""
+    rng = np.random.default_rng(5000 + seed)
+    d = int(rng.choice([64, 128]))
+    G = int(rng.choice([1, 2, 3, 4, 5, 6, 7, 8]))
+    Hkv = int(rng.integers(1, 5))
+    B = int(rng.integers(4, 13))
+    gran = [int(g) for g in rng.choice([16, 32, 48, 64, 128], size=Hkv)]
+    seq_len = [int(x) for x in rng.integers(2000, 30000, size=B)]
+    sink = int(rng.choice([0, 64, 100]))
+    window = int(rng.choice([0, 256, 300]))
+    bud = rng.choice([0.0, 0.05, 0.3, 1.0], size=(B, Hkv * G), p=[0.1, 0.3, 0.3, 0.3]).astype(np.float32)
+    wl = W.Workload(name=f"medium{seed}", n_q_heads=Hkv * G, n_kv_heads=Hkv, head_dim=d, seq_len=seq_len, gran=gran,
+                    sink_tokens=sink, window_tokens=window, budget_frac=bud, seed=seed,
+                    outlier_channels=int(rng.choice([0, 4])), q_mode=str(rng.choice(["normal", "near_key"])))
+    print(f"seed={seed} d={d} G={G} Hkv={Hkv} B={B} gran={gran} tokens={sum(seq_len)}", flush=True)
+    t = W.make_layer(wl)
+    ref = run_oracle(wl, t)
+    gp = GpuProblem(wl, t, k_max=ref["k_max"])
+    gp.summarize()
+    assert np.array_equal(bf16_bits_to_f64(W.to_u16(gp.S))[: ref["S"].shape[0]], bf16_bits_to_f64(ref["S"]))
+    idx, cnt = gp.select()
+    compare_selection(idx.cpu().numpy(), cnt.cpu().numpy(), ref["idx"], ref["cnt"], ref["gap"], ref["kth"],
+                      ref["scores"], None)
+    out = gp.decode(ref["idx"], ref["cnt"]).cpu().numpy()
+    assert np.abs(out.astype(np.float64) - ref["out"]).max() < TOL
+    assert np.array_equal(gp.decode(ref["idx"], ref["cnt"]).cpu().numpy(), out)  # same bits on a second run
