@@ -208,6 +208,9 @@ __device__ __forceinline__ void finish_split(Split& sp, int padded_total) {
   }
 }
 
+struct FullSlice { static constexpr bool value = true; };
+struct PartialSlice { static constexpr bool value = false; };
+
 template <int kD, int kG>
 __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* __restrict__ q,
                                                      const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
@@ -338,7 +341,9 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
       const int e = sl / spb;
       const uint32_t ent = __builtin_amdgcn_readfirstlane(s_ent[e - pe]);
       const uint32_t mask = ent & 255u;
-      const int t0 = (int)(ent >> 8) * geo.g + (sl - e * spb) * 16 + tslot;
+      const int t_first = (int)(ent >> 8) * geo.g + (sl - e * spb) * 16;  // first token of the slice
+      const int t0 = t_first + tslot;
+      const bool full = t_first + 16 <= geo.n_tokens;  // wave-uniform; false only in a sequence's last block
       uint4 kraw[kLoads], vraw[kLoads];
 #pragma unroll
       for (int i = 0; i < kLoads; ++i) {
@@ -347,6 +352,11 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
         vraw[i] = stream_load16(Vb + row);
       }
 
+      // The slice's arithmetic, compiled twice: kFull drops every per-row validity test.  Logits stay
+      // unscaled (log2(e)/sqrt(D) is folded into the exponent's fused multiply-add); the running maxima
+      // m_run are therefore unscaled too and are scaled when the partial is written.
+      auto compute = [&](auto full_tag) {
+      constexpr bool kFull = decltype(full_tag)::value;
       if constexpr (kHeadMajor) {
 #pragma unroll
         for (int r = 0; r < kG; ++r) {
@@ -356,24 +366,25 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
             float sp[kLoads];
 #pragma unroll
             for (int i = 0; i < kLoads; ++i) {
-              const bool valid = t0 + i * kTPL < geo.n_tokens;
+              const bool valid = kFull || t0 + i * kTPL < geo.n_tokens;
               float dot = dot2_bf16(qv.x, kraw[i].x, 0.f);
               dot = dot2_bf16(qv.y, kraw[i].y, dot);
               dot = dot2_bf16(qv.z, kraw[i].z, dot);
               dot = dot2_bf16(qv.w, kraw[i].w, dot);
-              dot = group_sum<kLanes>(dot) * q_scale;
+              dot = group_sum<kLanes>(dot);
               sp[i] = valid ? dot : kNegBig;
             }
             float mx = sp[0];
 #pragma unroll
             for (int i = 1; i < kLoads; ++i) mx = fmaxf(mx, sp[i]);
             const float m_new = fmaxf(m_run[r], mx);
-            const float alpha = __builtin_amdgcn_exp2f(m_run[r] - m_new);
+            const float alpha = __builtin_amdgcn_exp2f((m_run[r] - m_new) * q_scale);
+            const float m_scaled = m_new * q_scale;
             float psum = 0.f;
 #pragma unroll
             for (int i = 0; i < kLoads; ++i) {
-              const bool valid = t0 + i * kTPL < geo.n_tokens;
-              sp[i] = valid ? __builtin_amdgcn_exp2f(sp[i] - m_new) : 0.f;
+              const bool valid = kFull || t0 + i * kTPL < geo.n_tokens;
+              sp[i] = valid ? __builtin_amdgcn_exp2f(fmaf(sp[i], q_scale, -m_scaled)) : 0.f;
               psum += sp[i];
             }
             l_run[r] = l_run[r] * alpha + psum;
@@ -396,7 +407,7 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
         float sp[kG][kLoads];
 #pragma unroll
         for (int i = 0; i < kLoads; ++i) {
-          const bool valid = t0 + i * kTPL < geo.n_tokens;
+          const bool valid = kFull || t0 + i * kTPL < geo.n_tokens;
 #pragma unroll
           for (int r = 0; r < kG; ++r) {
             if (mask & (1u << r)) {
@@ -404,7 +415,7 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
               dot = dot2_bf16(qp[r].y, kraw[i].y, dot);
               dot = dot2_bf16(qp[r].z, kraw[i].z, dot);
               dot = dot2_bf16(qp[r].w, kraw[i].w, dot);
-              dot = group_sum<kLanes>(dot) * q_scale;
+              dot = group_sum<kLanes>(dot);
               sp[r][i] = valid ? dot : kNegBig;
             }
           }
@@ -417,12 +428,13 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
 #pragma unroll
             for (int i = 1; i < kLoads; ++i) mx = fmaxf(mx, sp[r][i]);
             const float m_new = fmaxf(m_run[r], mx);
-            const float alpha = __builtin_amdgcn_exp2f(m_run[r] - m_new);
+            const float alpha = __builtin_amdgcn_exp2f((m_run[r] - m_new) * q_scale);
+            const float m_scaled = m_new * q_scale;
             float psum = 0.f;
 #pragma unroll
             for (int i = 0; i < kLoads; ++i) {
-              const bool valid = t0 + i * kTPL < geo.n_tokens;
-              sp[r][i] = valid ? __builtin_amdgcn_exp2f(sp[r][i] - m_new) : 0.f;
+              const bool valid = kFull || t0 + i * kTPL < geo.n_tokens;
+              sp[r][i] = valid ? __builtin_amdgcn_exp2f(fmaf(sp[r][i], q_scale, -m_scaled)) : 0.f;
               psum += sp[r][i];
             }
             l_run[r] = l_run[r] * alpha + psum;
@@ -447,6 +459,8 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
           }
         }
       }
+      };  // compute
+      if (full) compute(FullSlice{}); else compute(PartialSlice{});
     }
     }  // pieces
 
@@ -460,7 +474,7 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
       float M = m_run[r];
 #pragma unroll
       for (int off = kLanes; off < 64; off <<= 1) M = fmaxf(M, __shfl_xor(M, off, kWave));
-      const float w = __builtin_amdgcn_exp2f(m_run[r] - M);
+      const float w = __builtin_amdgcn_exp2f((m_run[r] - M) * q_scale);
       float lw = l_run[r] * w;
 #pragma unroll
       for (int off = kLanes; off < 64; off <<= 1) lw += __shfl_xor(lw, off, kWave);
@@ -489,13 +503,13 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
       float o = 0.f, L = 0.f;
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
-        const float sc = __builtin_amdgcn_exp2f(s_red[w][r][kD] - M);
+        const float sc = __builtin_amdgcn_exp2f((s_red[w][r][kD] - M) * q_scale);
         o += s_red[w][r][c] * sc;
         L += s_red[w][r][kD + 1] * sc;
       }
       acc_part[((int64_t)slot * kG + r) * kD + c] = o;
       if (c == 0) {
-        ml_part[((int64_t)slot * kG + r) * 2] = M;
+        ml_part[((int64_t)slot * kG + r) * 2] = M * q_scale;  // the merge works in the scaled log2 domain
         ml_part[((int64_t)slot * kG + r) * 2 + 1] = L;
       }
     }
