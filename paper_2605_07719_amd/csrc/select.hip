@@ -50,9 +50,12 @@ __device__ __forceinline__ float key32_to_float(uint32_t k) {
 // ---------------------------------------------------------------------------------------------------
 // MFMA operand layout (v_mfma_f32_16x16x32_bf16): lane l supplies A[m = l % 16][k = 8 (l / 16) .. + 8]
 // and B[k = 8 (l / 16) .. + 8][n = l % 16]; it receives D[m = 4 (l / 16) + i][n = l % 16], i = 0..3.
-// Here n = candidate within a tile of 16, k = position in the [mn | mx] row, and the A rows are
-//   m = 0..7 : [q- | q+] of head m of the group      (-> s~, from B)
-//   m = 8..15: [|q-| | |q+|] of head m - 8            (-> a~, from |B|)
+// Here n = candidate within a tile of 16, k = position in the [mn | mx] row, and A row
+//   m = 4 (h % 4) + 2 (h / 4)     is [q- | q+] of head h of the group       (-> s~, from B)
+//   m = 4 (h % 4) + 2 (h / 4) + 1 is [|q-| | |q+|] of head h                (-> a~, from |B|)
+// so that result register 0 of the lanes 16 x .. 16 x + 15 is head x's score of the tile's 16 candidates
+// (register 2: head x + 4; registers 1 and 3: the magnitude sums): one store instruction of the whole
+// wave writes the scores of four heads, and one cross-lane reduction per register serves four heads.
 // The summaries are loaded straight into the B layout (each lane 16 bytes of its own row).  Staging
 // them through LDS with fully coalesced loads was measured to be about twice slower, and loading with
 // four neighbouring lanes per row followed by a wave-wide permutation made no difference.
@@ -85,8 +88,8 @@ __device__ __forceinline__ void score_tiles(const Params& P, const uint16_t* __r
   // q- keeps the negative elements, q+ the others; the magnitude rows drop the sign.
   uint4 a_op[kSlabs];
   {
-    const int head = n & 7;
-    const bool want_abs = n >= 8;
+    const int head = (n >> 2) + 4 * ((n >> 1) & 1);
+    const bool want_abs = (n & 1) != 0;
     auto part = [&](uint32_t v, bool is_mx) -> uint32_t {
       const uint32_t neg = ((v >> 15) & 0x00010001u) * 0xffffu;  // 0xffff in every half whose sign bit is set
       const uint32_t kept = is_mx ? (v & ~neg) : (v & neg);
@@ -104,7 +107,6 @@ __device__ __forceinline__ void score_tiles(const Params& P, const uint16_t* __r
     }
   }
 
-  const int head_row = (4 * r) & 7;  // this lane's D rows are heads head_row .. head_row + 3
   for (int tile = tile_first; tile < tile_end; ++tile) {
 #pragma unroll
     for (int s = 0; s < kSlabs; ++s) cur[s] = nxt[s];
@@ -120,22 +122,19 @@ __device__ __forceinline__ void score_tiles(const Params& P, const uint16_t* __r
                                                     __builtin_bit_cast(bf16x8_t, va), d_a, 0, 0, 0);
     }
     const int cand = tile * 16 + n;
-    if (r < 2 && cand < n_cand) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-        if (head_row + i < P.group)
-          approx[((((int64_t)b * P.n_kv_heads + j) * mag_stride + tile) * P.group + head_row + i) * 16 + n] = d_s[i];
-    }
-    // maximum magnitude over the tile's 16 candidates (clamped duplicates repeat a real candidate)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      float m = d_a[i];
+    for (int half = 0; half < 2; ++half) {  // heads r and r + 4
+      if (4 * half >= P.group) break;  // wave-uniform
+      const int head = r + 4 * half;
+      if (head < P.group && cand < n_cand)
+        approx[((((int64_t)b * P.n_kv_heads + j) * mag_stride + tile) * P.group + head) * 16 + n] = d_s[2 * half];
+      // maximum magnitude over the tile's 16 candidates (clamped duplicates repeat a real candidate)
+      float m = d_a[2 * half + 1];
       m = fmaxf(m, dpp_f<kDppXor1>(m));
       m = fmaxf(m, dpp_f<kDppXor2>(m));
       m = fmaxf(m, dpp_f<kDppHalfMirror>(m));
       m = fmaxf(m, dpp_f<kDppMirror>(m));
-      if (r >= 2 && n == 0 && head_row + i < P.group)
-        mag_tile[((int64_t)b * P.n_q_heads + j * P.group + head_row + i) * mag_stride + tile] = m;
+      if (n == 0 && head < P.group) mag_tile[((int64_t)b * P.n_q_heads + j * P.group + head) * mag_stride + tile] = m;
     }
   }
 }
