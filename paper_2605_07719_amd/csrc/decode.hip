@@ -229,7 +229,8 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
   constexpr bool kHeadMajor = kG >= 6;
   // (Requesting the next slice before the current one is consumed costs 32 more registers and never paid
   // for the resident wave it takes away: the loads in flight come from the resident waves.)
-  extern __shared__ int s_prefix[];     // [n_groups + 1] exclusive prefix of slices per group
+  extern __shared__ int s_prefix[];     // [n_groups + 1] exclusive prefix of (padded) slices per group, then
+                                        // [n_groups] per group: slices it really has | slices per block << 24
   __shared__ float s_red[4][kG][kD + 2];
   __shared__ int s_scan[4];
   __shared__ uint32_t s_ent[kEntriesPerPiece];
@@ -239,15 +240,22 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int chunk = lane % kLanes, tslot = lane / kLanes;
   const int n_groups = P.batch * P.n_kv_heads;
+  int* s_real = s_prefix + n_groups + 1;  // a segment then starts without a round trip to list lengths and block sizes
 
   // ---- the global slice sequence and its division, computed identically by every workgroup --------
   Split split;
   {
     const int per = (n_groups + 255) / 256;
     const int g_lo = min(tid * per, n_groups), g_hi = min(g_lo + per, n_groups);
-    auto slices_of = [&](int g) { return ucount[g] * ((int)P.gran[g % P.n_kv_heads] >> 4); };
+    // one round trip to global memory (list lengths and block sizes together); the later passes read LDS
     int local = 0;
-    for (int g = g_lo; g < g_hi; ++g) local += slices_of(g);
+    for (int g = g_lo; g < g_hi; ++g) {
+      const int spb = (int)P.gran[g % P.n_kv_heads] >> 4;
+      const int n = ucount[g] * spb;
+      s_real[g] = n | (spb << 24);
+      local += n;
+    }
+    auto slices_of = [&](int g) { return s_real[g] & 0xffffff; };  // this thread's own writes
     int incl = block_incl_scan(local, s_scan);
     split = make_split(s_scan[0] + s_scan[1] + s_scan[2] + s_scan[3], (int)gridDim.x);
     const int al = split.align;
@@ -301,12 +309,20 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
     // ---- one segment: slices [s0, seg_end) of the sequence, all inside group `grp` ------------------
     const int seg_end = min(s1, s_prefix[grp + 1]);
     const int b = grp / P.n_kv_heads, j = grp % P.n_kv_heads;
-    const Geo geo = geometry(P, b, j);
-    const int spb = geo.g >> 4;  // 16-token slices per block
+    const int spb = s_real[grp] >> 24;  // 16-token slices per block
     // slices relative to the group's list (the end of a padded group is clipped to the list's length)
-    const int l0 = s0 - s_prefix[grp], l1 = min(seg_end - s_prefix[grp], ucount[grp] * spb);
+    const int l0 = s0 - s_prefix[grp], l1 = min(seg_end - s_prefix[grp], s_real[grp] & 0xffffff);
     const int e_lo = l0 / spb, e_hi = (l1 - 1) / spb;                  // union entries touched (inclusive)
     const uint32_t* entries = uni + (int64_t)grp * union_cap;
+    // The first 256 union entries are requested here, together with q and the sequence's length and base
+    // (everything a segment needs from global memory before its K/V rows: one round trip).
+    uint32_t ent_next = e_lo + tid <= e_hi ? entries[e_lo + tid] : 0u;
+    struct { int g, n_tokens; } geo;
+    geo.g = spb << 4;
+    {
+      const int n = P.seq_len[b];
+      geo.n_tokens = n < 0 ? 0 : (n > P.max_seq_len ? P.max_seq_len : n);
+    }
     const int64_t head_base = P.seq_base[b] + (int64_t)j * P.kv_head_stride + chunk * 8;
     const uint16_t* Kb = K + head_base;
     const uint16_t* Vb = V + head_base;
@@ -332,8 +348,9 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
     // the segment's union entries pass through LDS in pieces, so the per-slice address chain starts from LDS
     for (int pe = e_lo; pe <= e_hi; pe += kEntriesPerPiece) {
     __syncthreads();  // the previous piece's readers are done
-    if (pe + tid <= e_hi) s_ent[tid] = entries[pe + tid];
+    s_ent[tid] = ent_next;
     __syncthreads();
+    if (pe + kEntriesPerPiece + tid <= e_hi) ent_next = entries[pe + kEntriesPerPiece + tid];  // in flight during this piece
     const int p_lo = max(l0, pe * spb), p_hi = min(l1, (pe + kEntriesPerPiece) * spb);
 
     for (int sl = p_lo + wave; sl < p_hi; sl += 4) {
@@ -605,7 +622,7 @@ static hipError_t launch_attend(const Params& P, const void* q, const void* K, c
                                 const int32_t* ucount, const DecodeWorkspace& W, int32_t* sched, float* acc_part,
                                 float* ml_part, int n_cu, hipStream_t stream) {
   static int wg_per_cu = 0;  // occupancy of this instantiation, queried once
-  const size_t lds = (size_t)(P.batch * P.n_kv_heads + 1) * sizeof(int);
+  const size_t lds = (size_t)(2 * P.batch * P.n_kv_heads + 1) * sizeof(int);
   if (wg_per_cu == 0) {
     int n = 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, attend_kernel<kD, kG>, 256, lds) != hipSuccess || n < 1) n = 1;
