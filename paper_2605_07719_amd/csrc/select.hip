@@ -192,13 +192,13 @@ __global__ __launch_bounds__(256) void score_stream_kernel(Params P, const uint1
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n_groups = P.batch * P.n_kv_heads;
   int* s_tiles = reinterpret_cast<int*>(s_rowbase + n_groups);  // [n_groups + 1] exclusive prefix of tiles
-  int* s_ncand = s_tiles + n_groups + 1;                        // [n_groups] candidates
+  uint16_t* s_ncand = reinterpret_cast<uint16_t*>(s_tiles + n_groups + 1);  // [n_groups] candidates (at most 2^15)
   {
     auto tiles_of = [&](int g) -> int {
       const int b = g / P.n_kv_heads, j = g - b * P.n_kv_heads;
       const bool any = group_selects(P, budget_frac, budget_blocks, b, j);
       const Geo geo = geometry(P, b, j);
-      s_ncand[g] = geo.n_cand;
+      s_ncand[g] = (uint16_t)geo.n_cand;
       s_rowbase[g] = P.sum_base[g] + geo.n_sink;
       return any ? (geo.n_cand + 15) >> 4 : 0;
     };
@@ -757,7 +757,8 @@ hipError_t launch_select(const Params& P, const void* q, const void* S, const fl
   const int mag_stride = W.mag_stride;
   {
     ScopedSlot prof(kSlotScore, stream);
-    const size_t lds = (size_t)P.batch * P.n_kv_heads * (sizeof(long long) + 2 * sizeof(int)) + sizeof(int);
+    // 14 bytes per group: 56 KiB at the largest supported batch * n_kv_heads (4096), inside the 64 KiB a workgroup may use
+    const size_t lds = (size_t)P.batch * P.n_kv_heads * (sizeof(long long) + sizeof(int) + sizeof(uint16_t)) + sizeof(int);
     const int64_t max_tiles = (int64_t)P.batch * P.n_kv_heads * mag_stride;
     const int64_t slots = (int64_t)n_cu * score_wg_per_cu(P.head_dim, lds);  // resident workgroups of the chip
     if (max_tiles <= 4 * slots) {  // at most one tile per wave slot

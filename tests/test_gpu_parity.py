@@ -42,6 +42,11 @@ def small_cases():
         "max_context_2e19": W.Workload(
             name="g", n_q_heads=2, n_kv_heads=1, head_dim=64, seq_len=[524288], gran=[16],
             sink_tokens=64, window_tokens=256, budget_frac=np.array([[0.02, 0.001]], dtype=np.float32), seed=7),
+        # batch * n_kv_heads at the library's limit (4096 groups): the per-group tables of the kernels' prologues
+        "max_groups_4096": W.Workload(
+            name="h", n_q_heads=16, n_kv_heads=8, head_dim=64,
+            seq_len=[int(x) for x in np.random.default_rng(8).integers(300, 901, size=512)], gran=[16, 32] * 4,
+            sink_tokens=64, window_tokens=128, budget_frac=np.full((512, 16), 0.2, dtype=np.float32), seed=8),
         "mha_g1": W.Workload(
             name="e", n_q_heads=3, n_kv_heads=3, head_dim=128, seq_len=[1500, 900], gran=[16, 32, 80],
             sink_tokens=64, window_tokens=256, budget_frac=np.full((2, 3), 0.15, dtype=np.float32), seed=5),
