@@ -47,6 +47,15 @@ def small_cases():
             name="h", n_q_heads=16, n_kv_heads=8, head_dim=64,
             seq_len=[int(x) for x in np.random.default_rng(8).integers(300, 901, size=512)], gran=[16, 32] * 4,
             sink_tokens=64, window_tokens=128, budget_frac=np.full((512, 16), 0.2, dtype=np.float32), seed=8),
+        # the largest number of KV heads (64) with every allowed block size
+        "kv_heads_64_all_block_sizes": W.Workload(
+            name="i", n_q_heads=64, n_kv_heads=64, head_dim=64, seq_len=[2000, 700, 1300],
+            gran=[16, 32, 48, 64, 80, 96, 112, 128] * 8, sink_tokens=64, window_tokens=256,
+            budget_frac=np.full((3, 64), 0.25, dtype=np.float32), seed=9),
+        # the longest context with a dense head: the longest index and union lists the kernels take
+        "max_context_dense_head": W.Workload(
+            name="j", n_q_heads=2, n_kv_heads=1, head_dim=64, seq_len=[524288], gran=[16],
+            sink_tokens=64, window_tokens=256, budget_frac=np.array([[1.0, 0.4]], dtype=np.float32), seed=10),
         "mha_g1": W.Workload(
             name="e", n_q_heads=3, n_kv_heads=3, head_dim=128, seq_len=[1500, 900], gran=[16, 32, 80],
             sink_tokens=64, window_tokens=256, budget_frac=np.full((2, 3), 0.15, dtype=np.float32), seed=5),
