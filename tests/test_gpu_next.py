@@ -88,6 +88,40 @@ def test_incremental_summaries_match_a_full_rebuild():
     del wl_old
 
 
+@pytest.mark.parametrize("case", ["one_token_each", "from_empty", "nothing_new"])
+def test_incremental_summaries_edge_cases(case):
+    """Decode steady state (one token per sequence, also one that opens a new block), a cache built from empty
+    by the append call alone, and an append of nothing."""
+    new = np.array([4097, 3201, 4100], dtype=np.int32)            # 4097: its last token opens a new block
+    prev, bound = {
+        "one_token_each": (new - 1, 1),
+        "from_empty": (np.zeros(3, dtype=np.int32), int(new.max())),
+        "nothing_new": (new.copy(), 1),
+    }[case]
+    wl = base_workload(seed=26, seq_len=new.tolist(), gran=[32, 80])
+    t = W.make_layer(wl)
+    gp = GpuProblem(wl, t)
+    pl = W.placement(wl)
+    old_layout = F.Layout.from_host(wl.n_q_heads, wl.n_kv_heads, wl.head_dim, prev, pl.seq_base, pl.kv_head_stride,
+                                    pl.token_stride, pl.sum_base.reshape(-1), pl.gran,
+                                    max_seq_len=int(pl.seq_len.max()))
+    _, K, _ = host_arrays(t)
+    ref_new = O.summarize(oracle_layout(wl), K, threads=THREADS)
+    if case == "nothing_new":
+        F.summarize(gp.layout, gp.K, gp.S)
+        torch.cuda.synchronize()
+        before = gp.S.clone()
+    else:
+        gp.S.fill_(float("nan"))
+        if case != "from_empty":
+            F.summarize(old_layout, gp.K, gp.S)
+    F.summarize_append(gp.layout, gp.K, gp.S, torch.from_numpy(prev).cuda(), bound)
+    torch.cuda.synchronize()
+    assert np.array_equal(bf16_bits_to_f64(W.to_u16(gp.S)), bf16_bits_to_f64(ref_new))
+    if case == "nothing_new":
+        assert np.array_equal(W.to_u16(gp.S), W.to_u16(before))
+
+
 def test_group_union_attention():
     wl = base_workload(seed=24, n_q_heads=14, n_kv_heads=2, gran=[32, 16], seq_len=[5000, 2100],
                        budget_frac=np.tile(np.array([0.02, 0.1, 0.0, 0.05, 0.3, 0.01, 0.07] * 2, np.float32), (2, 1)))
