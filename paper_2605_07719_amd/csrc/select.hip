@@ -56,31 +56,55 @@ __device__ __forceinline__ float key32_to_float(uint32_t k) {
 // so that result register 0 of the lanes 16 x .. 16 x + 15 is head x's score of the tile's 16 candidates
 // (register 2: head x + 4; registers 1 and 3: the magnitude sums): one store instruction of the whole
 // wave writes the scores of four heads, and one cross-lane reduction per register serves four heads.
-// The summaries are loaded straight into the B layout (each lane 16 bytes of its own row).  Staging
-// them through LDS with fully coalesced loads was measured to be about twice slower, and loading with
-// four neighbouring lanes per row followed by a wave-wide permutation made no difference.
+// Small steps load the summaries straight into the B layout (each lane 16 bytes of its own row: 64-byte
+// pieces of 16 rows per instruction, so two instructions share every 128-byte line).  The stream kernel
+// instead loads a tile as 8 KiB of whole lines with non-temporal loads (1 KiB contiguous per instruction)
+// and turns it into the B layout through a private, padded LDS region of the wave: 62 -> 53 us at 128K
+// context, batch 16.  (The same staging with ordinary loads is twice slower than no staging; four neighbouring
+// lanes per row followed by a wave-wide permutation made no difference.)
 // The magnitude sums are reduced to one maximum per tile and head before they leave the kernel (the
 // selection only needs their maximum per head).  The scores are stored tile-major,
 // [sequence][KV head][tile][head of the group][16], so that a wave's stores for a tile form one
 // contiguous run of G * 64 bytes (scattered 64-byte pieces cost ~10% of the kernel).
 
-// One wave scores tiles [tile_first, tile_end) of group (b, j): it requests the next tile's rows before it
-// multiplies the current one.  `rows` points at the group's first candidate row.
+// LDS of one wave for the staged tile walk: 16 rows of 2 kD bf16, each padded by 16 bytes so that the 16 lanes
+// that read the same piece of 16 different rows hit different banks.
 template <int kD>
+struct TileStage {
+  static constexpr int kPieces = kD / 4;      // 16-byte pieces per [mn | mx] row
+  static constexpr int kStride = kPieces + 1;  // row stride in pieces
+  uint4 piece[16 * kStride];
+};
+
+// One wave scores tiles [tile_first, tile_end) of group (b, j): it requests the next tile's rows before it
+// multiplies the current one.  `rows_base` points at the group's first candidate row.  With `stage` (the wave's
+// own LDS region) the rows arrive as whole lines and pass through LDS; without, they are loaded in the B layout.
+template <int kD, bool kStaged>
 __device__ __forceinline__ void score_tiles(const Params& P, const uint16_t* __restrict__ q,
                                             const uint16_t* __restrict__ rows_base, int n_cand, int b, int j,
                                             int tile_first, int tile_end, float* __restrict__ approx,
-                                            float* __restrict__ mag_tile, int mag_stride, int lane) {
+                                            float* __restrict__ mag_tile, int mag_stride, int lane,
+                                            TileStage<kD>* stage = nullptr) {
   constexpr int kRow = 2 * kD;       // elements of one [mn | mx] row
-  constexpr int kSlabs = kRow / 32;  // MFMA k-steps per row
+  constexpr int kSlabs = kRow / 32;  // MFMA k-steps per row = 1 KiB load instructions per tile
+  constexpr int kPieces = TileStage<kD>::kPieces, kStride = TileStage<kD>::kStride;
   const int n = lane & 15, r = lane >> 4;
-  const uint16_t* rows = rows_base + r * 8;
   uint4 cur[kSlabs], nxt[kSlabs];
   auto fetch = [&](int tile, uint4* dst) {
-    const int cand = min(tile * 16 + n, n_cand - 1);  // clamped: stays inside the candidates
-    const uint16_t* p = rows + (int64_t)cand * kRow;
+    if constexpr (kStaged) {
+      // instruction i takes pieces 64 i .. 64 i + 63 of the tile: rows are contiguous, so 1 KiB of whole lines
 #pragma unroll
-    for (int s = 0; s < kSlabs; ++s) dst[s] = *reinterpret_cast<const uint4*>(p + 32 * s);  // (plain: two loads share each 128-byte line)
+      for (int i = 0; i < kSlabs; ++i) {
+        const int f = i * 64 + lane;
+        const int cand = min(tile * 16 + f / kPieces, n_cand - 1);  // clamped: stays inside the candidates
+        dst[i] = stream_load16(rows_base + (int64_t)cand * kRow + (f % kPieces) * 8);
+      }
+    } else {
+      const int cand = min(tile * 16 + n, n_cand - 1);  // clamped: stays inside the candidates
+      const uint16_t* p = rows_base + r * 8 + (int64_t)cand * kRow;
+#pragma unroll
+      for (int s = 0; s < kSlabs; ++s) dst[s] = *reinterpret_cast<const uint4*>(p + 32 * s);
+    }
   };
   fetch(tile_first, nxt);
 
@@ -108,8 +132,26 @@ __device__ __forceinline__ void score_tiles(const Params& P, const uint16_t* __r
   }
 
   for (int tile = tile_first; tile < tile_end; ++tile) {
+    if constexpr (kStaged) {
+      // Only this wave touches its region, and a wave's LDS instructions execute in order: the fences keep the
+      // compiler from moving the reads of other lanes' data above the writes (and the next tile's writes above
+      // these reads); no barrier instruction is needed.
 #pragma unroll
-    for (int s = 0; s < kSlabs; ++s) cur[s] = nxt[s];
+      for (int i = 0; i < kSlabs; ++i) {
+        const int f = i * 64 + lane;
+        stage->piece[(f / kPieces) * kStride + f % kPieces] = nxt[i];
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+      for (int s = 0; s < kSlabs; ++s) cur[s] = stage->piece[n * kStride + 4 * s + r];  // pieces 4 s + r of row n
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+    } else {
+#pragma unroll
+      for (int s = 0; s < kSlabs; ++s) cur[s] = nxt[s];
+    }
     if (tile + 1 < tile_end) fetch(tile + 1, nxt);
     f32x4_t d_s = {0.f, 0.f, 0.f, 0.f}, d_a = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -171,7 +213,7 @@ __global__ __launch_bounds__(256) void score_grid_kernel(Params P, const uint16_
   const int tile = blockIdx.x * 4 + wave;
   if (tile * 16 >= geo.n_cand || !any) return;  // whole wave leaves
   const uint16_t* rows = S + (first_block + geo.n_sink) * (int64_t)(2 * kD);
-  score_tiles<kD>(P, q, rows, geo.n_cand, b, j, tile, tile + 1, approx, mag_tile, mag_stride, lane);
+  score_tiles<kD, false>(P, q, rows, geo.n_cand, b, j, tile, tile + 1, approx, mag_tile, mag_stride, lane);
 }
 
 // Larger steps: the tiles of all groups that need scores form one global tile sequence (its prefix over
@@ -179,7 +221,9 @@ __global__ __launch_bounds__(256) void score_grid_kernel(Params P, const uint16_
 // launch walks an equal contiguous share of it and rebuilds its A operand where the share crosses into
 // the next group.  Ragged batches, mixed block sizes and streaming groups therefore cost nothing in
 // balance (a grid over the longest sequence leaves most workgroups of a short one without work).
-template <int kD>
+// kStaged: whole-line loads through LDS (see above); the host falls back to the unstaged form where the group
+// tables leave no room for the stage.
+template <int kD, bool kStaged>
 __global__ __launch_bounds__(256) void score_stream_kernel(Params P, const uint16_t* __restrict__ q,
                                                            const uint16_t* __restrict__ S, float* __restrict__ approx,
                                                            float* __restrict__ mag_tile,
@@ -188,6 +232,7 @@ __global__ __launch_bounds__(256) void score_stream_kernel(Params P, const uint1
   // per group, filled by the prologue so that a wave entering a group starts its first loads at once:
   extern __shared__ long long s_rowbase[];  // [n_groups] first candidate's row (in blocks) inside the summaries
   __shared__ int s_scan[4];
+  __shared__ TileStage<kD> s_stage[kStaged ? 4 : 1];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n_groups = P.batch * P.n_kv_heads;
@@ -240,8 +285,8 @@ __global__ __launch_bounds__(256) void score_stream_kernel(Params P, const uint1
     const int b = grp / P.n_kv_heads, j = grp - b * P.n_kv_heads;
     const int tile_first = t - s_tiles[grp];
     const int tile_end = min(t_end, s_tiles[grp + 1]) - s_tiles[grp];
-    score_tiles<kD>(P, q, S + s_rowbase[grp] * (int64_t)(2 * kD), s_ncand[grp], b, j, tile_first, tile_end, approx,
-                    mag_tile, mag_stride, lane);
+    score_tiles<kD, kStaged>(P, q, S + s_rowbase[grp] * (int64_t)(2 * kD), s_ncand[grp], b, j, tile_first, tile_end,
+                             approx, mag_tile, mag_stride, lane, &s_stage[kStaged ? wave : 0]);
     t = s_tiles[grp] + tile_end;
     do ++grp; while (grp < n_groups && s_tiles[grp + 1] <= t);  // next group that has tiles
   }
@@ -732,18 +777,34 @@ __global__ __launch_bounds__(kT) void topk_reg_kernel(Params P, TopkArgs A) {
 
 float select_error_gamma() { return kGamma; }
 
-// Resident workgroups of the score kernel per CU, queried once per head size.
-static int score_wg_per_cu(int head_dim, size_t lds) {
-  static int cached[2] = {0, 0};
-  int& c = cached[head_dim == 128 ? 1 : 0];
-  if (c == 0) {
+// Resident workgroups of the stream score kernel per CU, queried once per instantiation.
+template <int kD, bool kStaged>
+static int score_wg_per_cu(size_t lds) {
+  static int cached = 0;
+  if (cached == 0) {
     int n = 0;
-    const hipError_t e = head_dim == 128 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, score_stream_kernel<128>, 256, lds)
-                                         : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, score_stream_kernel<64>, 256, lds);
+    const hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, score_stream_kernel<kD, kStaged>, 256, lds);
     if (e != hipSuccess || n < 1) n = 1;
-    c = n > 8 ? 8 : n;
+    cached = n > 8 ? 8 : n;
   }
-  return c;
+  return cached;
+}
+
+// Launches the score stage: the grid kernel for small steps, else the stream kernel.
+template <int kD, bool kStaged>
+static void launch_score(const Params& P, const uint16_t* q, const uint16_t* S, float* approx, float* mag,
+                         const float* budget_frac, const int32_t* budget_blocks, int mag_stride, size_t lds, int n_cu,
+                         hipStream_t stream) {
+  const int64_t max_tiles = (int64_t)P.batch * P.n_kv_heads * mag_stride;
+  const int64_t slots = (int64_t)n_cu * score_wg_per_cu<kD, kStaged>(lds);  // resident workgroups of the chip
+  if (max_tiles <= 4 * slots) {  // at most one tile per wave slot
+    const dim3 grid((mag_stride + 3) / 4, P.n_kv_heads, P.batch);
+    hipLaunchKernelGGL(score_grid_kernel<kD>, grid, dim3(256), 0, stream, P, q, S, approx, mag, budget_frac,
+                       budget_blocks, mag_stride);
+  } else {
+    hipLaunchKernelGGL((score_stream_kernel<kD, kStaged>), dim3((unsigned)slots), dim3(256), lds, stream, P, q, S,
+                       approx, mag, budget_frac, budget_blocks, mag_stride);
+  }
 }
 
 hipError_t launch_select(const Params& P, const void* q, const void* S, const float* budget_frac,
@@ -757,24 +818,22 @@ hipError_t launch_select(const Params& P, const void* q, const void* S, const fl
   const int mag_stride = W.mag_stride;
   {
     ScopedSlot prof(kSlotScore, stream);
-    // 14 bytes per group: 56 KiB at the largest supported batch * n_kv_heads (4096), inside the 64 KiB a workgroup may use
+    // Group tables of the stream kernel: 14 bytes per group, 56 KiB at the largest supported batch * n_kv_heads
+    // (4096).  A workgroup may use 64 KiB: the four waves' tile stages (33 KiB at d = 128, 17 KiB at d = 64) are
+    // used where they fit beside the tables (up to about 2200 / 3400 groups) and a wave has a stream to speak of
+    // (4 tiles or more; with fewer the extra LDS pass is pure latency: +0.6 us on the Qwen-shaped ragged batch).
     const size_t lds = (size_t)P.batch * P.n_kv_heads * (sizeof(long long) + sizeof(int) + sizeof(uint16_t)) + sizeof(int);
-    const int64_t max_tiles = (int64_t)P.batch * P.n_kv_heads * mag_stride;
-    const int64_t slots = (int64_t)n_cu * score_wg_per_cu(P.head_dim, lds);  // resident workgroups of the chip
-    if (max_tiles <= 4 * slots) {  // at most one tile per wave slot
-      const dim3 grid((mag_stride + 3) / 4, P.n_kv_heads, P.batch);
-      if (P.head_dim == 128)
-        hipLaunchKernelGGL(score_grid_kernel<128>, grid, dim3(256), 0, stream, P, (const uint16_t*)q,
-                           (const uint16_t*)S, approx, mag, budget_frac, budget_blocks, mag_stride);
-      else
-        hipLaunchKernelGGL(score_grid_kernel<64>, grid, dim3(256), 0, stream, P, (const uint16_t*)q,
-                           (const uint16_t*)S, approx, mag, budget_frac, budget_blocks, mag_stride);
-    } else if (P.head_dim == 128) {
-      hipLaunchKernelGGL(score_stream_kernel<128>, dim3((unsigned)slots), dim3(256), lds, stream, P,
-                         (const uint16_t*)q, (const uint16_t*)S, approx, mag, budget_frac, budget_blocks, mag_stride);
+    const size_t stage = 4 * (P.head_dim == 128 ? sizeof(TileStage<128>) : sizeof(TileStage<64>));
+    const int64_t waves = (int64_t)n_cu * 4 * (P.head_dim == 128 ? score_wg_per_cu<128, true>(lds) : score_wg_per_cu<64, true>(lds));
+    const bool staged = lds + stage + 64 <= 65536 && (int64_t)P.batch * P.n_kv_heads * mag_stride >= 4 * waves;
+    const uint16_t* q16 = (const uint16_t*)q;
+    const uint16_t* S16 = (const uint16_t*)S;
+    if (P.head_dim == 128) {
+      if (staged) launch_score<128, true>(P, q16, S16, approx, mag, budget_frac, budget_blocks, mag_stride, lds, n_cu, stream);
+      else launch_score<128, false>(P, q16, S16, approx, mag, budget_frac, budget_blocks, mag_stride, lds, n_cu, stream);
     } else {
-      hipLaunchKernelGGL(score_stream_kernel<64>, dim3((unsigned)slots), dim3(256), lds, stream, P,
-                         (const uint16_t*)q, (const uint16_t*)S, approx, mag, budget_frac, budget_blocks, mag_stride);
+      if (staged) launch_score<64, true>(P, q16, S16, approx, mag, budget_frac, budget_blocks, mag_stride, lds, n_cu, stream);
+      else launch_score<64, false>(P, q16, S16, approx, mag, budget_frac, budget_blocks, mag_stride, lds, n_cu, stream);
     }
   }
   hipError_t e = hipGetLastError();
