@@ -21,8 +21,9 @@
 //                  unit + group (strictly increasing along the slice sequence, hence unique).
 //   merge_kernel   per (sequence, query head): fuse the partial triples of the group's segments in
 //                  slot order (fixed order => reproducible results).
-// Logits are kept in the log2 domain (q is pre-multiplied by log2(e)/sqrt(D)) so the exponentials
-// are single v_exp_f32 instructions.
+// The exponentials are single v_exp_f32 instructions (base 2): dot products stay unscaled and the factor
+// log2(e)/sqrt(D) is folded into the exponent's fused multiply-add; the running maxima are scaled when a
+// partial is written, so the partials and the merge work in the scaled log2 domain.
 #include "fx_device.hpp"
 #include "fx_kernels.hpp"
 
