@@ -59,6 +59,12 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Params P, const int3
   const Geo geo = geometry(P, b, j);
   const int n_words = (geo.n_blocks + 3) >> 2;
   for (int w = tid; w < n_words; w += kPlanThreads) mask_words[w] = 0u;
+  // A head that keeps every candidate (a dense head: a valid list of n_cand entries is all of them) gets its
+  // bit from the block's position instead of from a walk over its list.
+  uint32_t dense_heads = 0u;
+#pragma unroll
+  for (int r = 0; r < kMaxGroup; ++r)
+    if (r < P.group && geo.n_cand > 0 && counts[r] >= geo.n_cand) dense_heads |= 1u << r;
   __syncthreads();
   // The heads' index lists are cut into pieces of FX_PLAN_PIECE entries and the pieces are dealt to the
   // waves round-robin, so short lists of different heads are walked concurrently and a long list is shared
@@ -71,7 +77,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Params P, const int3
     for (int r = 0; r < kMaxGroup; ++r) {
       if (r >= P.group) break;
       const int64_t slot = (int64_t)b * P.n_q_heads + j * P.group + r;
-      const int c = counts[r];
+      const int c = (dense_heads >> r) & 1u ? 0 : counts[r];
       const int32_t* list = idx + slot * P.k_max;
       for (int base = 0; base < c; base += kPiece, ++piece_no) {
         if (piece_no % kPlanWaves != wave) continue;
@@ -99,6 +105,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Params P, const int3
   auto mask_of = [&](int i, int end) -> uint32_t {
     const int ic = min(i, geo.n_blocks - 1);
     uint32_t m = (mask_words[ic >> 2] >> ((ic & 3) * 8)) & 255u;
+    m |= dense_heads;  // (sink and window blocks are overridden below)
     m = (as_union && m != 0u) ? all : m;
     m = (ic < geo.n_sink || ic >= geo.w0) ? all : m;
     return i < end ? m : 0u;
