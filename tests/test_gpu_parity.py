@@ -464,3 +464,27 @@ def test_long_contexts_take_the_staged_score_path(d):
     out = gp.decode().cpu().numpy().astype(np.float64)
     if differ == 0:
         assert np.abs(out - ref["out"]).max() < TOL
+
+
+def test_workspaces_can_be_reused_across_problems():
+    """A serving loop keeps one pair of workspaces, sized for its largest step, and runs steps of different
+    shapes through it: whatever an earlier, larger problem left there (union lists, prefix and split words,
+    a non-zero claim counter, partials, approximate scores) must not leak into a later, smaller one."""
+    big = small_cases()["d128_g7_ragged"]
+    small = W.Workload(name="small_after_big", n_q_heads=14, n_kv_heads=2, head_dim=128, seq_len=[900, 1300],
+                       gran=[16, 48], sink_tokens=64, window_tokens=256,
+                       budget_frac=np.full((2, 14), 0.3, dtype=np.float32), seed=31)
+    t_big, t_small = W.make_layer(big), W.make_layer(small)
+    ref_big, ref_small = run_oracle(big, t_big), run_oracle(small, t_small)
+    gp_big = GpuProblem(big, t_big, k_max=ref_big["k_max"])
+    gp_small = GpuProblem(small, t_small, k_max=ref_small["k_max"])
+    assert gp_small.ws_select.numel() <= gp_big.ws_select.numel()
+    assert gp_small.ws_decode.numel() <= gp_big.ws_decode.numel()
+    gp_small.ws_select, gp_small.ws_decode = gp_big.ws_select, gp_big.ws_decode  # one pair for both
+    for gp, ref in ((gp_big, ref_big), (gp_small, ref_small), (gp_big, ref_big), (gp_small, ref_small)):
+        gp.summarize()
+        idx, cnt = gp.select()
+        compare_selection(idx.cpu().numpy(), cnt.cpu().numpy(), ref["idx"], ref["cnt"], ref["gap"], ref["kth"],
+                          ref["scores"], None)
+        out = gp.decode(ref["idx"], ref["cnt"]).cpu().numpy().astype(np.float64)
+        assert np.abs(out - ref["out"]).max() < TOL
