@@ -126,3 +126,21 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(F, "LIB_PATH", "/nonexistent/libfluxion.so")
     with pytest.raises(ImportError):
         F.lib()
+
+
+def test_product_and_oracle_do_not_reach_into_each_other():
+    """The oracle is test infrastructure: nothing under the package may import, load or run it, and the oracle
+    may not use the package's code (only the seeded input generators are shared, by the tests)."""
+    import pathlib
+    import re
+
+    root = pathlib.Path(__file__).resolve().parents[1]
+    pkg = root / "paper_2605_07719_amd"
+    for path in list(pkg.rglob("*.py")) + list(pkg.rglob("*.hip")) + list(pkg.rglob("*.hpp")) + list(pkg.rglob("*.cpp")):
+        text = path.read_text()
+        assert not re.search(r"^\s*(from|import)\s+oracle\b", text, re.M), path
+        assert "fx_oracle" not in text and "libfx_oracle" not in text, path
+    for path in (root / "oracle").rglob("*"):
+        if path.suffix in (".py", ".cpp", ".h", ".hpp"):
+            text = path.read_text()
+            assert "paper_2605_07719_amd" not in text and "libfluxion" not in text and "fluxion.h" not in text, path
