@@ -211,6 +211,28 @@ def test_candidate_counts_of_the_named_configurations():
         assert np.isfinite(O.scores(L, q, S, sink, window)).sum() == n_cand
 
 
+def test_sink_and_window_round_outward_to_whole_blocks():
+    """Token counts worked out by hand from the reading taken for sink / window given in tokens: N = 1000,
+    g = 48 (21 blocks, the last one holds 40 tokens), sink 100 tokens -> blocks 0..2 (144 tokens), window 300
+    tokens -> blocks floor(700 / 48) = 14 .. 20 (tokens 672 .. 999: 328 tokens), candidates 3 .. 13 (11 blocks);
+    a budget of 0.3 keeps ceil(3.3) = 4 of them; a head with budget 0 attends to 144 + 328 = 472 tokens."""
+    wl, t = make(44, [1000], [48], hq=2, hkv=1, sink=100, window=300)
+    L = oracle_layout(wl)
+    q, K, V = host_arrays(t)
+    S = O.summarize(L, K)
+    assert S.shape[0] == 21
+    sc = O.scores(L, q, S, 100, 300)
+    assert np.flatnonzero(np.isfinite(sc[0, 0])).tolist() == list(range(3, 14))
+    idx, cnt, _, _ = O.select(L, q, S, budget_frac=np.array([[0.3, 0.0]], np.float32), sink_tokens=100,
+                              window_tokens=300, k_max=11)
+    assert cnt.tolist() == [[4, 0]]
+    assert all(3 <= i <= 13 for i in idx[0, 0, :4])
+    tok0, _ = O.token_weights(L, q, K, V, idx, cnt, sink_tokens=100, window_tokens=300, b=0, h=0)
+    tok1, _ = O.token_weights(L, q, K, V, idx, cnt, sink_tokens=100, window_tokens=300, b=0, h=1)
+    assert tok1.tolist() == list(range(0, 144)) + list(range(672, 1000))
+    assert tok0.size == 472 + 4 * 48
+
+
 def test_short_context_has_no_candidates_and_is_dense():
     wl, t = make(40, [40, 16, 100], [16, 32], sink=32, window=64)
     L = oracle_layout(wl)
