@@ -335,7 +335,7 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
     const uint16_t* Kb = K + head_base;
     const uint16_t* Vb = V + head_base;
 
-    // q stays packed (2 bf16 per register); the 1/sqrt(D) and log2(e) factors are applied to the dot product
+    // q stays packed (2 bf16 per register) and unscaled (the softmax scale is applied in the exponent)
     uint4 qp[kHeadMajor ? 1 : kG];
     if constexpr (kHeadMajor) {  // visible to all waves after the barrier that precedes the first piece
       if (tid < kG * kLanes)
