@@ -80,8 +80,9 @@ typedef struct fx_layout {
  * Errors: INVALID_ARG (null/misaligned), UNSUPPORTED (layout outside the supported range), HIP. */
 fx_status fx_summarize(const fx_layout* layout, const void* K, void* summaries, void* stream);
 
-/* Incremental summaries for a cache that grew (decode appends tokens; blocks fill up and leave the local
- * window, where selection starts to need their summaries).  Recomputes, for every (b, j), only the blocks
+/* Incremental summaries for a cache that grew (Sec. 2.1: the metadata of a logical block is the per-channel
+ * minimum and maximum of the keys it holds, so a block's summary changes only while tokens are appended to it;
+ * decode appends tokens, blocks fill up and leave the local window, where selection starts to need them).  Recomputes, for every (b, j), only the blocks
  * that hold tokens at or after prev_len[b]; seq_len[b] is the length after the append.  The result equals
  * fx_summarize on the grown cache provided the summaries of the blocks before prev_len[b] were up to date.
  *   prev_len        DEVICE int32 [batch]: length of each sequence before the append (<= seq_len[b])
@@ -98,10 +99,16 @@ size_t fx_select_workspace_bytes(const fx_layout* layout);
 /* Block scoring and per-head top-k (Sec. 2.1: compare the query with the metadata of all key blocks,
  * then select the top-k blocks; Sec. 5.3: one block size per group, one budget per head).
  * For query head h of sequence b (KV head j = h / group) and every candidate block i
- *     score(i) = sum_c max(q[c] * min_i[c], q[c] * max_i[c])          (accumulated in fp64)
+ *     score(i) = sum_c max(q[c] * min_i[c], q[c] * max_i[c])
  * and the k_h candidates that come first in the order (score descending, index ascending) are kept,
  * with k_h = budget_blocks[b][h] if given, else ceil(budget_frac[b][h] * n_cand) evaluated in double,
  * clamped to [0, min(n_cand, k_max)].
+ * Contract on precision: the kept set is the one that order gives with every score evaluated from the exact
+ * products summed in double precision.  (How: scores are first computed approximately with a proven error
+ * bound; every candidate closer to the k-th score than that bound is re-scored in double before it is ranked.
+ * Two candidates whose double-precision scores agree to ~1e-16 relative may be ordered by summation order.)
+ * Budgets larger than k_max: budgets are device data, so this cannot be an argument error; such a head keeps
+ * its best k_max candidates and cnt reports k_max.  Size idx with k_max >= the largest k_h to avoid it.
  *   q              bf16 [batch][n_q_heads][head_dim]
  *   summaries      bf16, as written by fx_summarize for the same layout
  *   budget_frac    float [batch][n_q_heads], or NULL   } exactly one of the two
@@ -118,19 +125,6 @@ size_t fx_select_workspace_bytes(const fx_layout* layout);
 fx_status fx_select(const fx_layout* layout, const void* q, const void* summaries, const float* budget_frac,
                     const int32_t* budget_blocks, int32_t sink_tokens, int32_t window_tokens, int32_t k_max,
                     int32_t* idx, int32_t* cnt, void* workspace, size_t workspace_bytes, void* stream);
-
-/* Test aid: where fx_select leaves its intermediate values inside the workspace after a call.  Candidates
- * are numbered c = i - n_sink (block index minus the number of sink blocks) and handled in tiles of 16.
- * With G = n_q_heads / n_kv_heads, j = h / G and r = h % G, the approximate score of candidate c for (b, h) is
- * the float at byte offset
- *     *approx_offset + 4 * ((((b * n_kv_heads + j) * (*mag_stride) + c / 16) * G + r) * 16 + c % 16)
- * and the largest magnitude sum (the bound of the rounding error) over the tile of c is the float at
- *     *mag_offset + 4 * ((b * n_q_heads + h) * (*mag_stride) + c / 16).
- * `*gamma` is the factor of the bound |approx - exact| <= gamma * magnitude that the selection relies on;
- * `*row_stride` is the row length of the per-(b, h) block arrays (fallback keys).
- * Returns INVALID_ARG/UNSUPPORTED for a bad layout. */
-fx_status fx_select_workspace_view(const fx_layout* layout, size_t* approx_offset, size_t* mag_offset,
-                                   int64_t* row_stride, int64_t* mag_stride, float* gamma);
 
 /* Bytes of scratch fx_sparse_decode needs (HOST computation; depends on the layout's host fields,
  * k_max, sink_tokens and window_tokens).  Returns 0 if the arguments are invalid. */
@@ -178,13 +172,16 @@ fx_status fx_sparse_decode_union(const fx_layout* layout, const void* q, const v
  *   l_cpu         number of keys selection runs over (the candidate tokens)
  *   candidates    int32 [n_candidates], e.g. {16, 32, 64, 128}
  *   gran          int32 [n_kv_heads], written;  budget float [n_q_heads], written (feeds fx_select's budget_frac)
- *   volume        double [n_kv_heads] or NULL, written: V at the chosen size (the task priority of Sec. 6.2)
+ *   volume        double [n_kv_heads] or NULL, written: V at the chosen size.  Informational: the paper orders its
+ *                 CPU/GPU task queue by it (Sec. 6.2); this library balances by bytes inside one launch and
+ *                 consumes no priority
  * Errors: INVALID_ARG. */
 fx_status fx_choose_granularity(int32_t n_q_heads, int32_t n_kv_heads, const float* bgt0, const float* slope,
                                 const uint8_t* streaming, int64_t l_cpu, const int32_t* candidates,
                                 int32_t n_candidates, int32_t* gran, float* budget, double* volume);
 
-/* Summary pyramid: summaries of a coarser block size from finer ones, exactly (a block of r*g tokens is r
+/* Summary pyramid (Sec. 2.1: blocks are logical, so the same cache can be viewed at several block sizes; Sec. 5.3
+ * picks the size per group and step): summaries of a coarser block size from finer ones, exactly (a block of r*g tokens is r
  * blocks of g tokens, so its minimum row is the minimum of their minimum rows and likewise for the maximum).
  * `fine` and `coarse` describe the same sequences (equal seq_len contents) and differ only in gran[] and
  * sum_base[]; coarse->gran[j] must be
@@ -193,6 +190,21 @@ fx_status fx_choose_granularity(int32_t n_q_heads, int32_t n_kv_heads, const flo
  * Errors: INVALID_ARG (null/misaligned, layouts that differ in shape), UNSUPPORTED, HIP. */
 fx_status fx_coarsen_summaries(const fx_layout* fine, const void* fine_summaries, const fx_layout* coarse,
                                void* coarse_summaries, void* stream);
+
+/* Test aid (not part of the method; the layout it describes is an implementation detail that may change with
+ * the kernels): where fx_select leaves its intermediate values inside the workspace after a call.  It exists so
+ * that a test can check the error bound the selection contract above rests on against an independent fp64 score.  Candidates
+ * are numbered c = i - n_sink (block index minus the number of sink blocks) and handled in tiles of 16.
+ * With G = n_q_heads / n_kv_heads, j = h / G and r = h % G, the approximate score of candidate c for (b, h) is
+ * the float at byte offset
+ *     *approx_offset + 4 * ((((b * n_kv_heads + j) * (*mag_stride) + c / 16) * G + r) * 16 + c % 16)
+ * and the largest magnitude sum (the bound of the rounding error) over the tile of c is the float at
+ *     *mag_offset + 4 * ((b * n_q_heads + h) * (*mag_stride) + c / 16).
+ * `*gamma` is the factor of the bound |approx - exact| <= gamma * magnitude that the selection relies on;
+ * `*row_stride` is the row length of the per-(b, h) block arrays (fallback keys).
+ * Returns INVALID_ARG/UNSUPPORTED for a bad layout. */
+fx_status fx_select_workspace_view(const fx_layout* layout, size_t* approx_offset, size_t* mag_offset,
+                                   int64_t* row_stride, int64_t* mag_stride, float* gamma);
 
 /* Measurement aid (not part of the method).  While enabled, fx_select and fx_sparse_decode bracket every
  * kernel they launch with HIP events recorded on the caller's stream; fx_profile_read waits for the

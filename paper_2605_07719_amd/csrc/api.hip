@@ -2,6 +2,9 @@
 // Every check that does not need the device happens before the first HIP call.
 #include "../../include/fluxion.h"
 
+#include <atomic>
+#include <mutex>
+
 #include "fx_device.hpp"
 #include "fx_kernels.hpp"
 
@@ -51,16 +54,16 @@ fx_status make_params(const fx_layout* L, int32_t sink_tokens, int32_t window_to
   return FX_OK;
 }
 
+// Compute units of the current device (queried once per device).
 int compute_units() {
-  static int n_cu = 0;
-  if (n_cu == 0) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
-      n = 256;
-    n_cu = n;
+  static std::atomic<int> cached[fx::kMaxDevices];
+  const int dev = fx::current_device();
+  int n = cached[dev].load(std::memory_order_relaxed);
+  if (n == 0) {
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+    cached[dev].store(n, std::memory_order_relaxed);
   }
-  return n_cu;
+  return n;
 }
 
 }  // namespace
@@ -217,7 +220,8 @@ static fx_status sparse_decode_impl(const fx_layout* layout, const void* q, cons
   if (!aligned16(q) || !aligned16(K) || !aligned16(V) || !aligned16(workspace)) return FX_ERR_INVALID_ARG;
   if (workspace_bytes < fx::carve_decode(P).total) return FX_ERR_WORKSPACE_TOO_SMALL;
   P.group_union = group_union;
-  return fx::launch_decode(P, q, K, V, idx, cnt, out, workspace, compute_units(), static_cast<hipStream_t>(stream)) ==
+  return fx::launch_decode(P, q, K, V, idx, cnt, out, workspace, fx::kMaxUnits, compute_units(),
+                           static_cast<hipStream_t>(stream)) ==
                  hipSuccess
              ? FX_OK
              : FX_ERR_HIP;

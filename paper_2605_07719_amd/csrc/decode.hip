@@ -24,6 +24,8 @@
 // The exponentials are single v_exp_f32 instructions (base 2): dot products stay unscaled and the factor
 // log2(e)/sqrt(D) is folded into the exponent's fused multiply-add; the running maxima are scaled when a
 // partial is written, so the partials and the merge work in the scaled log2 domain.
+#include <atomic>
+
 #include "fx_device.hpp"
 #include "fx_kernels.hpp"
 
@@ -45,6 +47,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Params P, const int3
                                                    int32_t* __restrict__ claim_counter) {
   extern __shared__ uint32_t mask_words[];  // one byte of head mask per block, 4 blocks per word
   __shared__ int scratch[kPlanWaves];
+  __shared__ uint32_t s_not_dense;
   const int b = blockIdx.y, j = blockIdx.x, tid = threadIdx.x;
   const int grp = b * P.n_kv_heads + j;
   int counts[kMaxGroup];  // requested before the geometry so they arrive together with the sequence length
@@ -59,25 +62,30 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Params P, const int3
   const Geo geo = geometry(P, b, j);
   const int n_words = (geo.n_blocks + 3) >> 2;
   for (int w = tid; w < n_words; w += kPlanThreads) mask_words[w] = 0u;
-  // A head that keeps every candidate (a dense head: a valid list of n_cand entries is all of them) gets its
-  // bit from the block's position instead of from a walk over its list.
-  uint32_t dense_heads = 0u;
+  // A head whose list is exactly the candidates in ascending order (what fx_select writes for a dense head) gets
+  // its bit from the block's position.  The list is still read once and compared entry by entry -- any other
+  // list of that length (duplicates, junk, an external selector's fixed-size list on a short sequence) fails the
+  // comparison and is walked like every other list -- but the comparison needs no LDS atomics.
+  uint32_t maybe_dense = 0u;
 #pragma unroll
   for (int r = 0; r < kMaxGroup; ++r)
-    if (r < P.group && geo.n_cand > 0 && counts[r] >= geo.n_cand) dense_heads |= 1u << r;
+    if (r < P.group && geo.n_cand > 0 && counts[r] == geo.n_cand) maybe_dense |= 1u << r;
+  if (tid == 0) s_not_dense = 0u;
   __syncthreads();
   // The heads' index lists are cut into pieces of FX_PLAN_PIECE entries and the pieces are dealt to the
   // waves round-robin, so short lists of different heads are walked concurrently and a long list is shared
   // by all waves; a lane keeps all index loads of a piece in flight before the LDS atomics that consume them.
-  {
+  const int wave = tid >> 6, lane = tid & 63;
+  auto walk = [&](uint32_t heads, uint32_t verify) {
     constexpr int kPiece = FX_PLAN_PIECE;
-    const int wave = tid >> 6, lane = tid & 63;
     int piece_no = 0;
 #pragma unroll
     for (int r = 0; r < kMaxGroup; ++r) {
       if (r >= P.group) break;
+      if (!((heads >> r) & 1u)) continue;
+      const bool check = (verify >> r) & 1u;
       const int64_t slot = (int64_t)b * P.n_q_heads + j * P.group + r;
-      const int c = (dense_heads >> r) & 1u ? 0 : counts[r];
+      const int c = counts[r];
       const int32_t* list = idx + slot * P.k_max;
       for (int base = 0; base < c; base += kPiece, ++piece_no) {
         if (piece_no % kPlanWaves != wave) continue;
@@ -87,13 +95,30 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Params P, const int3
           const int e = base + u * 64 + lane;
           i[u] = e < c ? list[e] : -1;
         }
+        if (check) {
+          bool ok = true;
 #pragma unroll
-        for (int u = 0; u < kPiece / 64; ++u)
-          if (i[u] >= 0 && i[u] < geo.n_blocks) atomicOr(&mask_words[i[u] >> 2], (1u << r) << ((i[u] & 3) * 8));
+          for (int u = 0; u < kPiece / 64; ++u) {
+            const int e = base + u * 64 + lane;
+            ok = ok && (e >= c || i[u] == geo.n_sink + e);
+          }
+          if (!ok) atomicOr(&s_not_dense, 1u << r);
+        } else {
+#pragma unroll
+          for (int u = 0; u < kPiece / 64; ++u)
+            if (i[u] >= 0 && i[u] < geo.n_blocks) atomicOr(&mask_words[i[u] >> 2], (1u << r) << ((i[u] & 3) * 8));
+        }
       }
     }
-  }
+  };
+  walk((1u << P.group) - 1u, maybe_dense);
   __syncthreads();
+  const uint32_t failed = s_not_dense;  // workgroup-uniform
+  const uint32_t dense_heads = maybe_dense & ~failed;
+  if (failed) {
+    walk(failed, 0u);
+    __syncthreads();
+  }
   // Ordered compaction in two sweeps.  A wave owns a contiguous share of the blocks and walks it 64
   // blocks at a time: the first sweep counts the kept blocks (ballot + popcount, no barrier), one barrier
   // exchanges the wave totals, the second sweep writes each kept block at wave base + running count
@@ -110,7 +135,6 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Params P, const int3
     m = (ic < geo.n_sink || ic >= geo.w0) ? all : m;
     return i < end ? m : 0u;
   };
-  const int wave = tid >> 6, lane = tid & 63;
   const int per_wave = (geo.n_blocks + kPlanThreads - 1) / kPlanThreads * 64;  // a multiple of 64; all waves together cover n_blocks
   const int w_lo = min(wave * per_wave, geo.n_blocks), w_hi = min(w_lo + per_wave, geo.n_blocks);
   // four 64-block steps per iteration keep four LDS reads in flight
@@ -625,22 +649,35 @@ __global__ __launch_bounds__(256) void merge_kernel(Params P, const int32_t* __r
   }
 }
 
+// Resident workgroups of attend_kernel<kD, kG> per compute unit on the current device (queried once per device).
+template <int kD, int kG>
+static int attend_wg_per_cu(size_t lds) {
+  static std::atomic<int> cached[kMaxDevices];
+  const int dev = current_device();
+  int n = cached[dev].load(std::memory_order_relaxed);
+  if (n == 0) {
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, attend_kernel<kD, kG>, 256, lds) != hipSuccess || n < 1) n = 1;
+    n = n > 8 ? 8 : n;
+    cached[dev].store(n, std::memory_order_relaxed);
+  }
+  return n;
+}
+
+static size_t attend_lds_bytes(const Params& P) { return (size_t)(2 * P.batch * P.n_kv_heads + 1) * sizeof(int); }
+
+template <int kD, int kG>
+static int attend_grid(const Params& P, int n_cu) {
+  const int grid = n_cu * attend_wg_per_cu<kD, kG>(attend_lds_bytes(P));
+  return grid > kMaxUnits ? kMaxUnits : grid;
+}
+
 template <int kD, int kG>
 static hipError_t launch_attend(const Params& P, const void* q, const void* K, const void* V, const uint32_t* uni,
                                 const int32_t* ucount, const DecodeWorkspace& W, int32_t* sched, float* acc_part,
                                 float* ml_part, int n_cu, hipStream_t stream) {
-  static int wg_per_cu = 0;  // occupancy of this instantiation, queried once
-  const size_t lds = (size_t)(2 * P.batch * P.n_kv_heads + 1) * sizeof(int);
-  if (wg_per_cu == 0) {
-    int n = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, attend_kernel<kD, kG>, 256, lds) != hipSuccess || n < 1) n = 1;
-    wg_per_cu = n > 8 ? 8 : n;
-  }
-  int grid = n_cu * wg_per_cu;
-  if (grid > kMaxUnits) grid = kMaxUnits;
-  hipLaunchKernelGGL((attend_kernel<kD, kG>), dim3(grid), dim3(256), lds, stream, P, (const uint16_t*)q,
-                     (const uint16_t*)K, (const uint16_t*)V, uni, ucount, W.union_cap, sched, acc_part, ml_part,
-                     W.slots_cap);
+  hipLaunchKernelGGL((attend_kernel<kD, kG>), dim3(attend_grid<kD, kG>(P, n_cu)), dim3(256), attend_lds_bytes(P), stream,
+                     P, (const uint16_t*)q, (const uint16_t*)K, (const uint16_t*)V, uni, ucount, W.union_cap, sched,
+                     acc_part, ml_part, W.slots_cap);
   return hipGetLastError();
 }
 
@@ -658,9 +695,21 @@ static hipError_t dispatch_group(const Params& P, const void* q, const void* K, 
   return hipErrorInvalidValue;
 }
 
+int attend_launch_size(const Params& P, int n_cu) {
+  switch (P.group) {
+#define FX_CASE(G) \
+  case G:          \
+    return P.head_dim == 128 ? attend_grid<128, G>(P, n_cu) : attend_grid<64, G>(P, n_cu);
+    FX_CASE(1) FX_CASE(2) FX_CASE(3) FX_CASE(4) FX_CASE(5) FX_CASE(6) FX_CASE(7) FX_CASE(8)
+#undef FX_CASE
+  }
+  return kMaxUnits;
+}
+
 hipError_t launch_decode(const Params& P, const void* q, const void* K, const void* V, const int32_t* idx,
-                         const int32_t* cnt, float* out, void* workspace, int n_cu, hipStream_t stream) {
-  const DecodeWorkspace W = carve_decode(P);
+                         const int32_t* cnt, float* out, void* workspace, int carve_units, int n_cu,
+                         hipStream_t stream) {
+  const DecodeWorkspace W = carve_decode(P, carve_units);
   char* ws = static_cast<char*>(workspace);
   uint32_t* uni = reinterpret_cast<uint32_t*>(ws + W.union_off);
   int32_t* ucount = reinterpret_cast<int32_t*>(ws + W.ucount_off);

@@ -10,6 +10,14 @@
 namespace fx {
 
 constexpr size_t kAlign = 256;
+
+// Per-device caches (occupancy, compute units) are indexed by the current device ordinal.
+constexpr int kMaxDevices = 64;
+inline int current_device() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) dev = 0;
+  return dev;
+}
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 // fx_select scratch: the approximate scores (fp32, tile-major [sequence][KV head][tile][head of group][16]),
@@ -54,7 +62,9 @@ struct DecodeWorkspace {
   size_t ml_off;      // float  [slots_cap][group][2]   partial running maximum (log2 domain) and sum
   size_t total;
 };
-inline DecodeWorkspace carve_decode(const Params& P) {
+// `max_units`: upper bound of the attention kernel's launch size the carving must hold partial results for
+// (the public size query cannot ask the device and uses kMaxUnits).
+inline DecodeWorkspace carve_decode(const Params& P, int max_units = kMaxUnits) {
   DecodeWorkspace W;
   const int n_groups = P.batch * P.n_kv_heads;
   int64_t ucap = 0;
@@ -66,7 +76,7 @@ inline DecodeWorkspace carve_decode(const Params& P) {
     if (u > ucap) ucap = u;
   }
   if (ucap < 1) ucap = 1;
-  const int64_t slots = (int64_t)kMaxUnits * (1 + kClaimedPerWg) + 2 * n_groups + 8;
+  const int64_t slots = (int64_t)max_units * (1 + kClaimedPerWg) + 2 * n_groups + 8;
   W.union_cap = (int32_t)ucap;
   W.slots_cap = (int32_t)slots;
   size_t off = 0;
@@ -108,7 +118,11 @@ hipError_t launch_coarsen(const Params& Pf, const Params& Pc, const void* Sf, vo
 hipError_t launch_select(const Params& P, const void* q, const void* S, const float* budget_frac,
                          const int32_t* budget_blocks, int32_t* idx, int32_t* cnt, void* workspace, int n_cu,
                          hipStream_t stream);
+// Workgroups the attention kernel is launched with on the current device (resident slots, at most kMaxUnits).
+int attend_launch_size(const Params& P, int n_cu);
+// `carve_units`: the max_units the caller sized `workspace` with (>= attend_launch_size).
 hipError_t launch_decode(const Params& P, const void* q, const void* K, const void* V, const int32_t* idx,
-                         const int32_t* cnt, float* out, void* workspace, int n_cu, hipStream_t stream);
+                         const int32_t* cnt, float* out, void* workspace, int carve_units, int n_cu,
+                         hipStream_t stream);
 
 }  // namespace fx

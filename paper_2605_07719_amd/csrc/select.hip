@@ -18,6 +18,8 @@
 //   fp64 scores (up to fp64 summation order, ~1e-16), while the bulk of the work runs at the speed
 //   the summaries stream from HBM.  If the band holds more candidates than fit in LDS (masses of
 //   identical blocks) the head falls back to exact scores for all candidates and a 64-bit radix select.
+#include <atomic>
+
 #include "fx_device.hpp"
 #include "fx_kernels.hpp"
 
@@ -777,17 +779,19 @@ __global__ __launch_bounds__(kT) void topk_reg_kernel(Params P, TopkArgs A) {
 
 float select_error_gamma() { return kGamma; }
 
-// Resident workgroups of the stream score kernel per CU, queried once per instantiation.
+// Resident workgroups of the stream score kernel per CU on the current device, queried once per device.
 template <int kD, bool kStaged>
 static int score_wg_per_cu(size_t lds) {
-  static int cached = 0;
-  if (cached == 0) {
-    int n = 0;
+  static std::atomic<int> cached[kMaxDevices];
+  const int dev = current_device();
+  int n = cached[dev].load(std::memory_order_relaxed);
+  if (n == 0) {
     const hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, score_stream_kernel<kD, kStaged>, 256, lds);
     if (e != hipSuccess || n < 1) n = 1;
-    cached = n > 8 ? 8 : n;
+    n = n > 8 ? 8 : n;
+    cached[dev].store(n, std::memory_order_relaxed);
   }
-  return cached;
+  return n;
 }
 
 // Launches the score stage: the grid kernel for small steps, else the stream kernel.

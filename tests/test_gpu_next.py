@@ -148,7 +148,10 @@ def test_group_union_attention():
 
 
 def test_streaming_groups_are_skipped_and_still_correct():
-    """One whole group has budget 0 (streaming heads): its summaries need not be read; outputs still match."""
+    """KV head 0 of every sequence is a group of streaming heads (budget 0).  Its summaries are poisoned with NaN
+    and its part of the score workspace with a marker: the selection and the outputs must not be affected, and
+    the marker must survive fx_select (the score stage never visited the group, so it had no reason to read its
+    summaries), while the other group's scores were written."""
     bud = np.full((3, 8), 0.1, dtype=np.float32)
     bud[:, :4] = 0.0
     wl = base_workload(seed=25, budget_frac=bud)
@@ -156,10 +159,26 @@ def test_streaming_groups_are_skipped_and_still_correct():
     ref = run_oracle(wl, t)
     gp = GpuProblem(wl, t, k_max=ref["k_max"])
     gp.summarize()
+    pl = gp.pl
+    for b in range(wl.batch):                                      # the streaming group's summary rows -> NaN
+        lo = int(pl.sum_base[b, 0])
+        gp.S[lo : lo + int(pl.n_blocks[b, 0])] = float("nan")
     gp.ws_select.fill_(0xFF)                                       # stale workspace must not matter
     idx, cnt = gp.select()
+    torch.cuda.synchronize()
     assert int(cnt[:, :4].abs().sum()) == 0
     compare_selection(idx.cpu().numpy(), cnt.cpu().numpy(), ref["idx"], ref["cnt"], ref["gap"], ref["kth"],
                       ref["scores"], None)
+    v = F.select_workspace_view(gp.layout)
+    G, n_tiles = wl.group, v["mag_stride"]
+    raw = gp.ws_select.cpu().numpy()
+    approx = raw[v["approx_offset"] : v["approx_offset"] + 4 * wl.batch * wl.n_q_heads * n_tiles * 16]
+    approx = approx.reshape(wl.batch, wl.n_kv_heads, n_tiles * G * 16 * 4)
+    assert (approx[:, 0] == 0xFF).all()                            # streaming group: never written
+    assert not (approx[:, 1] == 0xFF).all()                        # the selecting group: scored
+    mags = raw[v["mag_offset"] : v["mag_offset"] + 4 * wl.batch * wl.n_q_heads * n_tiles]
+    mags = mags.reshape(wl.batch, wl.n_q_heads, n_tiles * 4)
+    assert (mags[:, :4] == 0xFF).all() and not (mags[:, 4:] == 0xFF).all()
     out = gp.decode().cpu().numpy().astype(np.float64)
+    assert np.isfinite(out).all()
     assert np.abs(out - ref["out"]).max() < TOL

@@ -254,3 +254,28 @@ def test_group_union_token_set_and_special_cases():
     a = O.sparse_attention(L1, q1, K1, V1, i1, c1, sink_tokens=16, window_tokens=32, group_union=True)
     c = O.sparse_attention(L1, q1, K1, V1, i1, c1, sink_tokens=16, window_tokens=32)
     assert np.array_equal(a, c)
+
+
+def test_layer_step_is_select_followed_by_sparse_attention():
+    """The wrapper the benchmark's cpu_baseline leg times must be exactly the two pinned routines chained:
+    same index lists, same counts, same output bits, for fractional and for integer budgets, with threads."""
+    wl = W.Workload(
+        name="step", n_q_heads=6, n_kv_heads=2, head_dim=64, seq_len=[900, 333, 1500], gran=[16, 32],
+        sink_tokens=20, window_tokens=70, seed=12,
+        budget_frac=np.array([[0.0, 0.05, 0.3, 1.0, 0.11, 0.5]] * 3, dtype=np.float32),
+    )
+    t = W.make_layer(wl)
+    L = oracle_layout(wl)
+    q, K, V = host_arrays(t)
+    S = O.summarize(L, K)
+    k_max = L.max_blocks()
+    kw = dict(sink_tokens=wl.sink_tokens, window_tokens=wl.window_tokens)
+    for budgets in (dict(budget_frac=wl.budget_frac), dict(budget_blocks=np.array([[0, 3, 1, 40, 7, 2]] * 3, np.int32))):
+        idx, cnt, _, _ = O.select(L, q, S, k_max=k_max, **budgets, **kw)
+        out = O.sparse_attention(L, q, K, V, idx, cnt, **kw)
+        for threads in (1, 3):
+            idx2, cnt2, out2 = O.layer_step(L, q, K, V, S, k_max=k_max, threads=threads, **budgets, **kw)
+            assert np.array_equal(idx2, idx) and np.array_equal(cnt2, cnt)
+            assert np.array_equal(out2, out)
+    with pytest.raises(ValueError):
+        O.layer_step(L, q, K, V, S, k_max=2, budget_frac=wl.budget_frac, **kw)
