@@ -7,13 +7,17 @@ step re-reads a cache-resident layer.  fx_summarize runs once per layer before t
 (it is a cache-build step, not a per-token step) and is reported separately.
 
 Prints ONE JSON line.  `value` is microseconds per layer-step on the headline workload (the
-Llama-3-8B-shaped 32-layer stack at 32K context, batch 1, budget 0.05); `roofline` describes the
-dominant kernel (split-K attention) on that workload; `workloads` carries the same figures for the
-128K-context configurations; `cpu_baseline` is the fp64 oracle timed on this machine's host cores.
+Llama-3-8B-shaped 32-layer stack at 32K context, batch 1, budget 0.05).  `roofline` describes the
+dominant kernel (split-K attention) at the point the HBM target is defined on: 128K context, batch 16,
+budget 0.05 (`roofline.workload` names it; the same object for the latency-bound headline workload is
+`roofline_32k`).  `workloads` carries the figures of every other configuration, each with a sampled
+check against the oracle (near-tie heads, max abs error) and the oracle's own time on that sample.
+`cpu_baseline` is the fp64 oracle timed on this machine's host cores on the headline workload.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -172,6 +176,8 @@ def measure(ls: LayerSet, steps: int, warmup: int, use_graph: bool) -> dict:
     unique = float(np.mean(dec_unique))
     step_ms = graph_ms if graph_ms is not None else eager_ms
     attend_gbps = unique / (kern_ms["attend"] * 1e-3) / 1e9
+    decode_call_ms = kern_ms["plan"] + kern_ms["attend"] + kern_ms["merge"]  # the whole fx_sparse_decode call
+    decode_gbps = unique / (decode_call_ms * 1e-3) / 1e9
     return {
         "workload": wl.name,
         "us_per_layer_step": step_ms * 1e3,
@@ -183,6 +189,8 @@ def measure(ls: LayerSet, steps: int, warmup: int, use_graph: bool) -> dict:
         "select_bytes": float(np.mean(sel_bytes)),
         "attend_GBps": attend_gbps,
         "attend_frac_of_hbm_peak": attend_gbps / HBM_PEAK_GBPS,
+        "decode_call_GBps": decode_gbps,
+        "decode_call_frac_of_hbm_peak": decode_gbps / HBM_PEAK_GBPS,
         "step_GBps": (unique + float(np.mean(sel_bytes))) / (step_ms * 1e-3) / 1e9,
         "summarize_ms_per_layer": sum_ms,
         "summarize_GBps": T.summarize_bytes(pl.seq_len, pl.gran, wl.head_dim) / (sum_ms * 1e-3) / 1e9,
@@ -193,18 +201,32 @@ def measure(ls: LayerSet, steps: int, warmup: int, use_graph: bool) -> dict:
     }
 
 
+def csrc_hash() -> str:
+    """Hash of the kernel sources: the counter-derived traffic figures under profiles/ are valid for one build."""
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2605_07719_amd", "csrc")
+    for name in sorted(os.listdir(d)):
+        h.update(name.encode())
+        h.update(open(os.path.join(d, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
 def profiled_traffic(workload: str, kernel: str = "attend_kernel"):
     """HBM bytes per launch of the dominant kernel measured with rocprofv3 hardware counters (FETCH_SIZE and
-    WRITE_SIZE runs, summarised under profiles/); None if no profile of this workload is committed."""
+    WRITE_SIZE runs, summarised under profiles/traffic.txt).  None if no figure for this workload is committed
+    or if the kernel sources changed since the counters were read (the file records the hash of csrc/)."""
     path = os.path.join(ROOT, "profiles", "traffic.txt")
+    value, stamp = None, None
     try:
         for line in open(path):
             f = line.split()
+            if len(f) == 3 and f[0] == "#" and f[1] == "csrc_sha16":
+                stamp = f[2]
             if len(f) == 3 and f[0] == workload and f[1] == kernel:
-                return float(f[2])
+                value = float(f[2])
     except OSError:
-        pass
-    return None
+        return None
+    return value if stamp == csrc_hash() else None
 
 
 def stream_probe(n_bytes=4 << 30) -> dict:
@@ -269,6 +291,35 @@ def output_deviation(ls: LayerSet) -> dict:
     return res
 
 
+def union_step_times(ls: LayerSet, steps: int = 16) -> dict:
+    """The layer-step with group-union attention on the selections of fx_select (every head of a group attends
+    over the union of the group's selections): per-kernel HIP-event times and the attention kernel's rate."""
+    import torch
+
+    from paper_2605_07719_amd import fluxion as F
+
+    wl = ls.wl
+
+    def union_step(i):
+        q, K, V, S = ls.layers[i % len(ls.layers)]
+        F.select(ls.layout, q, S, budget_frac=ls.bf, budget_blocks=ls.bb, sink_tokens=wl.sink_tokens,
+                 window_tokens=wl.window_tokens, k_max=ls.k_max, idx=ls.idx, cnt=ls.cnt, workspace=ls.ws_sel)
+        F.sparse_decode(ls.layout, q, K, V, ls.idx, ls.cnt, k_max=ls.k_max, sink_tokens=wl.sink_tokens,
+                        window_tokens=wl.window_tokens, out=ls.out, workspace=ls.ws_dec, group_union=True)
+
+    for i in range(64):  # the GPU may have idled while the host worked: let the clocks come back up
+        union_step(i)
+    torch.cuda.synchronize()
+    F.profile_enable(True)
+    acc = {k: 0.0 for k in F.PROFILE_SLOTS}
+    for i in range(steps):
+        union_step(i)
+        for k, v in F.profile_read().items():
+            acc[k] += v / steps * 1e3
+    F.profile_enable(False)
+    return {"kernel_us": acc, "us_per_layer_step": sum(acc.values())}
+
+
 def next_rows(ls: LayerSet, steps: int = 16) -> dict:
     """Timings of the widened entry points on the workload of `ls`: group-union attention, the summary pyramid,
     incremental summaries and the host-side granularity/budget selector."""
@@ -292,25 +343,9 @@ def next_rows(ls: LayerSet, steps: int = 16) -> dict:
         return ev0.elapsed_time(ev1) / reps * 1e3  # us
 
     out = {"workload": wl.name}
-    # group-union attention on the selections of fx_select (every head of a group attends over the union)
-    def union_step(i):
-        q, K, V, S = ls.layers[i % len(ls.layers)]
-        F.select(ls.layout, q, S, budget_frac=ls.bf, budget_blocks=ls.bb, sink_tokens=wl.sink_tokens,
-                 window_tokens=wl.window_tokens, k_max=ls.k_max, idx=ls.idx, cnt=ls.cnt, workspace=ls.ws_sel)
-        F.sparse_decode(ls.layout, q, K, V, ls.idx, ls.cnt, k_max=ls.k_max, sink_tokens=wl.sink_tokens,
-                        window_tokens=wl.window_tokens, out=ls.out, workspace=ls.ws_dec, group_union=True)
-    for i in range(64):  # the GPU idled while the host counted bytes: let the clocks come back up
-        union_step(i)
-    torch.cuda.synchronize()
-    F.profile_enable(True)
-    acc = {k: 0.0 for k in F.PROFILE_SLOTS}
-    for i in range(steps):
-        union_step(i)
-        for k, v in F.profile_read().items():
-            acc[k] += v / steps * 1e3
-    F.profile_enable(False)
-    out["union_kernel_us"] = acc                      # HIP events around each kernel, as in measure()
-    out["union_us_per_layer_step"] = sum(acc.values())
+    uni = union_step_times(ls, steps)
+    out["union_kernel_us"] = uni["kernel_us"]          # HIP events around each kernel, as in measure()
+    out["union_us_per_layer_step"] = uni["us_per_layer_step"]
 
     # summary pyramid: coarse summaries at 4x the block size from the resident ones
     if all(int(g) * 4 <= 128 for g in pl.gran):
@@ -342,34 +377,86 @@ def next_rows(ls: LayerSet, steps: int = 16) -> dict:
     return out
 
 
-def cpu_baseline(wl, seconds=12.0) -> dict:
-    """The oracle, as it stands, on this machine's host cores: selection + sparse attention of one layer-step."""
+def sampled_oracle(ls: LayerSet, sample, seconds: float) -> dict:
+    """Outside every timed region: the GPU's layer 0 step against the oracle on the sequences `sample` (all their
+    heads), and the oracle's own time for the layer-step of those sequences on this machine's host cores.
+    Returns (parity figures, cpu baseline); the baseline is scaled linearly from the sample's tokens to the
+    workload's when the sample is not the whole batch."""
     import torch
 
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    from helpers import host_arrays, oracle_layout
+    from oracle import checks as C
     from oracle import fx_oracle as O
     from paper_2605_07719_amd import workloads as W
 
-    t = W.make_layer(wl, 0, device="cpu")
-    L = oracle_layout(wl)
-    q, K, V = host_arrays(t)
+    wl = ls.wl
+    q, K, V, S = ls.layers[0]
+    ls.step(0)
+    torch.cuda.synchronize()
+    idx_g, cnt_g = ls.idx[sample].cpu().numpy(), ls.cnt[sample].cpu().numpy()
+    out_g = ls.out[sample].cpu().numpy().astype(np.float64)
+    sub_wl, sub_t = W.subset(wl, W.LayerTensors(q=q, K=K, V=V), sample)
+    L = C.layout_for(sub_wl, W.placement(sub_wl))
+    qh, Kh, Vh = W.to_u16(sub_t.q), W.to_u16(sub_t.K), W.to_u16(sub_t.V)
+    del sub_t
     threads = O.default_threads()
-    S = O.summarize(L, K, threads=threads)
+    So = O.summarize(L, Kh, threads=threads)
     k_max = int(max(1, L.max_blocks()))
-    kw = dict(budget_frac=wl.budget_frac, budget_blocks=wl.budget_blocks, sink_tokens=wl.sink_tokens,
-              window_tokens=wl.window_tokens, k_max=k_max, threads=threads)
-    O.layer_step(L, q, K, V, S, **kw)  # warm-up
+    kw = dict(sink_tokens=wl.sink_tokens, window_tokens=wl.window_tokens)
+    bud = dict(budget_frac=sub_wl.budget_frac, budget_blocks=sub_wl.budget_blocks)
+
+    # ---- parity figures -------------------------------------------------------------------------
+    parity = {"sample": f"sequences {list(sample)} of layer 0, all {wl.n_q_heads} heads",
+              "heads_checked": int(cnt_g.size)}
+    pl, sub_pl = ls.pl, W.placement(sub_wl)
+    S_gpu = W.to_u16(S)
+    same_summaries = all(
+        np.array_equal(
+            C.bf16_bits_to_f64(S_gpu[int(pl.sum_base[b, j]): int(pl.sum_base[b, j]) + int(pl.n_blocks[b, j])]),
+            C.bf16_bits_to_f64(So[int(sub_pl.sum_base[n, j]): int(sub_pl.sum_base[n, j]) + int(pl.n_blocks[b, j])]))
+        for n, b in enumerate(sample) for j in range(wl.n_kv_heads))
+    parity["summaries_equal"] = bool(same_summaries)
+    idx_o, cnt_o, gap, kth = O.select(L, qh, So, k_max=k_max, threads=threads, **bud, **kw)
+    sc = O.scores(L, qh, So, wl.sink_tokens, wl.window_tokens, threads=threads)
+    try:
+        exempt, differ = C.compare_selection(idx_g, cnt_g, idx_o[..., : idx_g.shape[-1]], cnt_o, gap, kth, sc)
+        parity.update(selection_exact=True, exempt_near_tie_heads=int(exempt), heads_differing_inside_band=int(differ))
+    except AssertionError as e:  # a real mismatch: report it, never hide it
+        parity.update(selection_exact=False, selection_error=repr(e))
+    own = O.sparse_attention(L, qh, Kh, Vh, idx_g, cnt_g, threads=threads, **kw)
+    parity["max_abs_err"] = float(np.abs(out_g - own).max())
+    parity["max_abs_err_basis"] = "oracle attention over the blocks the GPU selected; tolerance 5e-3"
+
+    # ---- the oracle's own time -------------------------------------------------------------------
+    O.layer_step(L, qh, Kh, Vh, So, k_max=k_max, threads=threads, **bud, **kw)  # warm-up
     times = []
     t_end = time.time() + seconds
-    while time.time() < t_end or len(times) < 5:
+    while time.time() < t_end or len(times) < 3:
         t0 = time.perf_counter()
-        O.layer_step(L, q, K, V, S, **kw)
+        O.layer_step(L, qh, Kh, Vh, So, k_max=k_max, threads=threads, **bud, **kw)
         times.append(time.perf_counter() - t0)
+    scale = float(wl.total_tokens) / float(sub_wl.total_tokens)
+    whole = len(sample) == wl.batch
+    base = {
+        "value": float(np.median(times) * 1e6 * scale), "unit": "us per decode layer-step", "cores": threads,
+        "kind": "oracle", "workload": wl.name,
+        "sample": (f"{len(times)} layer-steps (selection + sparse attention, all {wl.n_q_heads} heads) of layer 0 of "
+                   f"{wl.name}, " + ("whole batch" if whole else
+                                     f"sequences {list(sample)} only ({sub_wl.total_tokens} of {wl.total_tokens} tokens), "
+                                     f"median scaled linearly by {scale:.2f}") + "; median"),
+    }
+    return parity, base
+
+
+def roofline_of(r: dict) -> dict:
+    """The `roofline` object of one measured workload (dominant kernel: split-K attention)."""
     return {
-        "value": float(np.median(times) * 1e6), "unit": "us per decode layer-step", "cores": threads, "kind": "oracle",
-        "sample": f"{len(times)} full layer-steps (selection + sparse attention, all {wl.n_q_heads} heads) of layer 0 "
-                  f"of {wl.name}; median",
+        "bound": "hbm", "kernel": "attend_kernel (split-K sparse attention)", "workload": r["workload"],
+        "achieved": r["attend_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": r["attend_frac_of_hbm_peak"],
+        "traffic": profiled_traffic(r["workload"]),
+        "bytes_per_launch": r["decode_unique_bytes"], "us_per_launch": r["kernel_us"]["attend"],
+        "frac_whole_decode_call": r["decode_call_frac_of_hbm_peak"],
+        "note": "frac = unique K/V bytes of the step / attend_kernel time / 8 TB/s (the figure the 70% target is "
+                "judged on); frac_whole_decode_call divides the same bytes by plan + attend + merge",
     }
 
 
@@ -380,10 +467,14 @@ def main():
     ap.add_argument("--warmup", type=int, default=32)
     ap.add_argument("--no-graph", action="store_true", help="time eager launches only")
     ap.add_argument("--no-extra", action="store_true", help="skip the 128K-context workloads")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle (timing and sampled parity check)")
     ap.add_argument("--only", default="", help="run only this extra workload as the headline (debug/profiling)")
     ap.add_argument("--budget", type=float, default=0.05)
+    ap.add_argument("--print-csrc-hash", action="store_true", help="print the hash profiles/traffic.txt is stamped with")
     args = ap.parse_args()
+    if args.print_csrc_hash:
+        print(csrc_hash())
+        return
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
         sys.exit(2)
@@ -397,55 +488,70 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     use_graph = not args.no_graph
+    with_oracle = not args.no_cpu_baseline
 
+    # name -> (workload, resident layers, sequences the oracle checks and is timed on)
     extras = {
-        "hbm_stress": lambda: (W.hbm_stress(budget=args.budget, n_layers=4), 4),
-        "hbm_stress_dense": lambda: (W.hbm_stress(budget=1.0, n_layers=2), 2),
-        "hbm_stress_0.02": lambda: (W.hbm_stress(budget=0.02, n_layers=4), 4),
-        "hbm_stress_0.1": lambda: (W.hbm_stress(budget=0.1, n_layers=4), 4),
-        "head_specific": lambda: (W.head_specific(n_layers=4), 4),
-        "qwen_ragged": lambda: (W.qwen_ragged(n_layers=4), 4),
+        "hbm_stress": lambda: (W.hbm_stress(budget=args.budget, n_layers=4), 4, [0]),
+        "hbm_stress_dense": lambda: (W.hbm_stress(budget=1.0, n_layers=2), 2, [0]),
+        "hbm_stress_0.02": lambda: (W.hbm_stress(budget=0.02, n_layers=4), 4, [0]),
+        "hbm_stress_0.1": lambda: (W.hbm_stress(budget=0.1, n_layers=4), 4, [0]),
+        "head_specific": lambda: (W.head_specific(n_layers=4), 4, [0]),
+        "qwen_ragged": lambda: (W.qwen_ragged(n_layers=4), 4, [0]),
+        # every head of a 7-head group on every block: the arithmetic-heaviest case of the attention kernel
+        "qwen_ragged_dense": lambda: (W.with_budget(W.qwen_ragged(n_layers=2), 1.0), 2, [0]),
     }
 
+    def run(ls, sample, oracle_seconds):
+        r = measure(ls, args.steps, args.warmup, use_graph)
+        base = None
+        if with_oracle:
+            r["parity"], base = sampled_oracle(ls, sample, oracle_seconds)
+        return r, base
+
+    baselines = []
+    nxt = None
     if args.only:
-        wl, nl = extras[args.only]()
-        head = measure(LayerSet(wl, nl), args.steps, args.warmup, use_graph)
+        wl, nl, sample = extras[args.only]()
+        head, base = run(LayerSet(wl, nl), sample, 3.0)
         head_wl = wl
     else:
         head_wl = W.llama_stack()
         head_ls = LayerSet(head_wl, head_wl.n_layers)
-        head = measure(head_ls, args.steps, args.warmup, use_graph)
+        head, base = run(head_ls, [0], 10.0)
         head["eq2_output_deviation"] = output_deviation(head_ls)
         del head_ls
         torch.cuda.empty_cache()
     log("[bench] headline:", json.dumps(head))
 
     others = []
-    nxt = None
     if not args.no_extra and not args.only:
         for name, mk in extras.items():
-            wl, nl = mk()
+            wl, nl, sample = mk()
+            wl.name = wl.name if not name.endswith("_dense") or "b1.0" in wl.name else wl.name + "_dense"
             ls = LayerSet(wl, nl)
-            r = measure(ls, max(8, args.steps // 4), max(4, args.warmup // 4), use_graph)
+            r, b = run(ls, sample, 2.0)
             log(f"[bench] {name}:", json.dumps(r))
             others.append(r)
+            if b is not None:
+                baselines.append(b)
             if name == "hbm_stress":
                 nxt = next_rows(ls)
                 log("[bench] widened entry points:", json.dumps(nxt))
+            if name == "qwen_ragged":
+                u = union_step_times(ls, min(args.steps, 16))
+                u["attend_frac_of_hbm_peak"] = r["decode_unique_bytes"] / (u["kernel_us"]["attend"] * 1e-6) / 1e9 / HBM_PEAK_GBPS
+                r["group_union"] = u  # same bytes as the per-head step: every head now works on every block of the union
             del ls
             torch.cuda.empty_cache()
 
     probe = stream_probe()
     log("[bench] stream probe:", json.dumps(probe))
-    head["attend_frac_of_stream_read"] = head["attend_GBps"] / probe["read_GBps"]
-    for r in others:
+    for r in [head] + others:
         r["attend_frac_of_stream_read"] = r["attend_GBps"] / probe["read_GBps"]
         r["attend_traffic_bytes"] = profiled_traffic(r["workload"])
 
-    base = None
-    if not args.no_cpu_baseline:
-        base = cpu_baseline(head_wl)
-
+    target = others[0] if others else head   # the 128K, batch 16, budget 0.05 point when it was run
     line = {
         "metric": "us per decode layer-step (fx_select + fx_sparse_decode)",
         "value": head["us_per_layer_step"],
@@ -462,7 +568,9 @@ def main():
         "data": "synthetic",
         "timing": "hip_graph_replay" if head["us_per_layer_step_graph"] is not None else "eager",
         "config": {
-            "workload": head["workload"], "batch": head["batch"], "context": head["max_context"],
+            "workload": f"{head['workload']} (value, ms_per_step, detail, cpu_baseline); roofline measured on "
+                        f"{target['workload']}",
+            "batch": head["batch"], "context": head["max_context"],
             "layers_resident": head["layers_resident"], "n_q_heads": head_wl.n_q_heads,
             "n_kv_heads": head_wl.n_kv_heads, "head_dim": head_wl.head_dim, "block_size": head_wl.gran,
             "budget": "per-head table" if head_wl.budget_frac is None or np.ptp(head_wl.budget_frac) > 0
@@ -470,22 +578,13 @@ def main():
             "sink_tokens": head_wl.sink_tokens, "window_tokens": head_wl.window_tokens,
         },
         "detail": head,
-        "roofline": {
-            "bound": "hbm", "kernel": "attend_kernel (split-K sparse attention)",
-            "achieved": head["attend_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-            "frac": head["attend_frac_of_hbm_peak"], "traffic": profiled_traffic(head["workload"]),
-            "bytes_per_launch": head["decode_unique_bytes"], "us_per_launch": head["kernel_us"]["attend"],
-        },
-        "roofline_128k": None if not others else {
-            "bound": "hbm", "kernel": "attend_kernel (split-K sparse attention)", "workload": others[0]["workload"],
-            "achieved": others[0]["attend_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-            "frac": others[0]["attend_frac_of_hbm_peak"], "traffic": others[0]["attend_traffic_bytes"],
-            "bytes_per_launch": others[0]["decode_unique_bytes"], "us_per_launch": others[0]["kernel_us"]["attend"],
-        },
+        "roofline": roofline_of(target),
+        "roofline_32k": roofline_of(head),
         "stream_probe": probe,
         "next_rows": nxt,
         "workloads": others,
         "cpu_baseline": base,
+        "cpu_baseline_workloads": baselines,
     }
     print(json.dumps(line), flush=True)
 
