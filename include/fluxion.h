@@ -40,7 +40,8 @@ typedef enum fx_status {
   FX_ERR_INVALID_ARG = 1,         /* null pointer, inconsistent sizes, misaligned pointer or stride      */
   FX_ERR_UNSUPPORTED = 2,         /* head_dim, group size, block size or context outside the built range */
   FX_ERR_WORKSPACE_TOO_SMALL = 3, /* workspace_bytes below what fx_*_workspace_bytes reports              */
-  FX_ERR_HIP = 4                  /* a HIP launch failed; hipGetLastError() has the cause                 */
+  FX_ERR_HIP = 4,                 /* a HIP launch failed; hipGetLastError() has the cause                 */
+  FX_ERR_SCRATCH_LIMIT = 5        /* fx_sparse_decode_static: the problem needs more than the built-in scratch */
 } fx_status;
 
 /* Static, never-NULL description of a status code. */
@@ -150,6 +151,25 @@ size_t fx_decode_workspace_bytes(const fx_layout* layout, int32_t k_max, int32_t
 fx_status fx_sparse_decode(const fx_layout* layout, const void* q, const void* K, const void* V, const int32_t* idx,
                            const int32_t* cnt, int32_t k_max, int32_t sink_tokens, int32_t window_tokens, float* out,
                            void* workspace, size_t workspace_bytes, void* stream);
+
+/* fx_sparse_decode for callers that cannot allocate device memory (code running under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc) and therefore cannot bring a workspace: the same computation,
+ * the same kernels and the same result bits as fx_sparse_decode, with the scratch taken from a buffer of
+ * FX_STATIC_SCRATCH_BYTES that is built into the library (each GPU the library runs on holds one copy of it
+ * from the first call on that GPU until the process ends).  The call allocates and frees nothing.
+ * Limit: the scratch the problem needs at this device's launch size -- union lists of
+ * batch * n_kv_heads * min(blocks, sink + window blocks + group * k_max) * 4 bytes plus partial results of
+ * (9 * launched workgroups + 2 * batch * n_kv_heads + 8) * group * (head_dim + 2) * 4 bytes -- must fit, else
+ * FX_ERR_SCRATCH_LIMIT is returned and nothing is enqueued (on MI355X every named configuration of up to 8
+ * heads per group at head_dim 128 fits).
+ * All calls on one GPU share that GPU's buffer: calls that may overlap in time on one GPU (different streams
+ * or threads) race; serialise them or use fx_sparse_decode with a workspace each.  Nothing in the buffer needs
+ * clearing between calls (the one counter that must start at zero is reset by the call's first kernel).
+ * Other arguments and errors as fx_sparse_decode. */
+#define FX_STATIC_SCRATCH_BYTES (48u << 20)
+fx_status fx_sparse_decode_static(const fx_layout* layout, const void* q, const void* K, const void* V,
+                                  const int32_t* idx, const int32_t* cnt, int32_t k_max, int32_t sink_tokens,
+                                  int32_t window_tokens, float* out, void* stream);
 
 /* Group-union variant of fx_sparse_decode: every query head of a GQA group attends to the union of the blocks
  * chosen by the heads of its group (plus sink and window).  The group's blocks are in registers for all its

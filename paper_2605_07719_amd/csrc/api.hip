@@ -116,6 +116,7 @@ const char* fx_status_string(fx_status status) {
     case FX_ERR_UNSUPPORTED: return "unsupported shape or size";
     case FX_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
     case FX_ERR_HIP: return "HIP launch failed";
+    case FX_ERR_SCRATCH_LIMIT: return "problem exceeds the built-in scratch buffer";
   }
   return "unknown status";
 }
@@ -221,8 +222,7 @@ static fx_status sparse_decode_impl(const fx_layout* layout, const void* q, cons
   if (workspace_bytes < fx::carve_decode(P).total) return FX_ERR_WORKSPACE_TOO_SMALL;
   P.group_union = group_union;
   return fx::launch_decode(P, q, K, V, idx, cnt, out, workspace, fx::kMaxUnits, compute_units(),
-                           static_cast<hipStream_t>(stream)) ==
-                 hipSuccess
+                           static_cast<hipStream_t>(stream)) == hipSuccess
              ? FX_OK
              : FX_ERR_HIP;
 }
@@ -240,6 +240,51 @@ fx_status fx_sparse_decode_union(const fx_layout* layout, const void* q, const v
                                  void* stream) {
   return sparse_decode_impl(layout, q, K, V, idx, cnt, k_max, sink_tokens, window_tokens, out, workspace,
                             workspace_bytes, stream, 1);
+}
+
+// ---- fx_sparse_decode for callers that cannot allocate ---------------------------------------------------------
+// The scratch of the decode stage (union lists, split description, claim counter, partial results) lives in a
+// file-scope device array instead of a caller-supplied workspace.  Every GPU the library runs on holds its own
+// copy of the array at its own address; the address is looked up once per device and that pointer -- never the
+// array's name, which in host code is only a stand-in -- is what the kernels receive.
+static __device__ __align__(256) unsigned char scratch[FX_STATIC_SCRATCH_BYTES];
+
+namespace {
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[fx::kMaxDevices];  // device address of `scratch` per device ordinal; guarded by the mutex
+
+// Device address of `scratch` on the current device, or nullptr.
+void* static_scratch() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= fx::kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+}  // namespace
+
+fx_status fx_sparse_decode_static(const fx_layout* layout, const void* q, const void* K, const void* V,
+                                  const int32_t* idx, const int32_t* cnt, int32_t k_max, int32_t sink_tokens,
+                                  int32_t window_tokens, float* out, void* stream) {
+  fx::Params P;
+  fx_status st = make_params(layout, sink_tokens, window_tokens, k_max, &P);
+  if (st != FX_OK) return st;
+  if (!q || !K || !V || !idx || !cnt || !out) return FX_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(K) || !aligned16(V)) return FX_ERR_INVALID_ARG;
+  // smallest possible carving (one unit): a problem that cannot fit at any launch size is refused on the host
+  if (fx::carve_decode(P, 1).total > (size_t)FX_STATIC_SCRATCH_BYTES) return FX_ERR_SCRATCH_LIMIT;
+  void* ws = static_scratch();
+  if (!ws) return FX_ERR_HIP;
+  const int n_cu = compute_units();
+  const int units = fx::attend_launch_size(P, n_cu);  // the attention kernel's launch size on this device
+  if (fx::carve_decode(P, units).total > (size_t)FX_STATIC_SCRATCH_BYTES) return FX_ERR_SCRATCH_LIMIT;
+  return fx::launch_decode(P, q, K, V, idx, cnt, out, ws, units, n_cu, static_cast<hipStream_t>(stream)) == hipSuccess
+             ? FX_OK
+             : FX_ERR_HIP;
 }
 
 }  // extern "C"

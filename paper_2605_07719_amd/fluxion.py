@@ -20,10 +20,10 @@ LIB_PATH = os.environ.get("FLUXION_LIB", os.path.join(_HERE, "libfluxion.so"))  
 EXPORTS = (
     "fx_status_string", "fx_summarize", "fx_select_workspace_bytes", "fx_select", "fx_decode_workspace_bytes",
     "fx_sparse_decode", "fx_profile_enable", "fx_profile_read", "fx_probe_read", "fx_probe_read_streaming", "fx_probe_copy", "fx_select_workspace_view", "fx_choose_granularity",
-    "fx_coarsen_summaries", "fx_summarize_append", "fx_sparse_decode_union",
+    "fx_coarsen_summaries", "fx_summarize_append", "fx_sparse_decode_union", "fx_sparse_decode_static",
 )
 
-FX_OK, FX_ERR_INVALID_ARG, FX_ERR_UNSUPPORTED, FX_ERR_WORKSPACE_TOO_SMALL, FX_ERR_HIP = range(5)
+FX_OK, FX_ERR_INVALID_ARG, FX_ERR_UNSUPPORTED, FX_ERR_WORKSPACE_TOO_SMALL, FX_ERR_HIP, FX_ERR_SCRATCH_LIMIT = range(6)
 
 
 class FluxionError(RuntimeError):
@@ -73,6 +73,8 @@ def lib() -> ctypes.CDLL:
             fn.restype = ctypes.c_int
             fn.argtypes = [ctypes.c_void_p] * 6 + [ctypes.c_int32] * 3 + [ctypes.c_void_p] * 2 + [
                 ctypes.c_size_t, ctypes.c_void_p]
+        L.fx_sparse_decode_static.restype = ctypes.c_int
+        L.fx_sparse_decode_static.argtypes = [ctypes.c_void_p] * 6 + [ctypes.c_int32] * 3 + [ctypes.c_void_p] * 2
         L.fx_summarize_append.restype = ctypes.c_int
         L.fx_summarize_append.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_int32, ctypes.c_void_p]
         L.fx_profile_enable.restype = ctypes.c_int
@@ -254,6 +256,21 @@ def sparse_decode(layout: Layout, q: torch.Tensor, K: torch.Tensor, V: torch.Ten
             _stream(stream),
         ),
         "fx_sparse_decode",
+    )
+
+
+def sparse_decode_static(layout: Layout, q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, idx: torch.Tensor,
+                         cnt: torch.Tensor, *, k_max: int, sink_tokens: int, window_tokens: int, out: torch.Tensor,
+                         stream=None) -> None:
+    """fx_sparse_decode_static: fx_sparse_decode with the scratch taken from the library's built-in buffer
+    (for callers that cannot allocate a workspace)."""
+    c = layout.c_struct()
+    _check(
+        lib().fx_sparse_decode_static(
+            ctypes.byref(c), _dptr(q), _dptr(K), _dptr(V), _dptr(idx), _dptr(cnt), k_max, sink_tokens,
+            window_tokens, _dptr(out), _stream(stream),
+        ),
+        "fx_sparse_decode_static",
     )
 
 

@@ -30,8 +30,8 @@ def test_library_exports_every_declared_function():
 
 def test_status_strings():
     assert F.status_string(F.FX_OK) == "ok"
-    texts = {F.status_string(s) for s in range(5)}
-    assert len(texts) == 5 and all(texts)
+    texts = {F.status_string(s) for s in range(6)}
+    assert len(texts) == 6 and all(texts)
     assert F.status_string(99)
 
 
@@ -114,6 +114,13 @@ def test_bad_arguments_are_rejected_before_any_launch():
     assert dec(p, odd, p, p, p, 8, 64, 256, p, p, need_dec, None) == INV
     assert dec(p, p, p, p, p, 8, 64, -5, p, p, need_dec, None) == INV
     assert dec(p, p, p, p, p, 8, 64, 256, p, p, need_dec - 1, None) == SMALL
+    # the variant with built-in scratch: same checks, and a problem no launch size could fit is refused on the host
+    stat = lambda L_, *a: lib.fx_sparse_decode_static(ctypes.byref(L_.c), *a)
+    assert stat(L, p, p, p, p, p, 8, 64, 256, None, None) == INV
+    assert stat(L, p, odd, p, p, p, 8, 64, 256, p, None) == INV
+    assert stat(L, p, p, p, p, p, 0, 64, 256, p, None) == INV
+    huge = HostLayout(batch=512, hq=8, hkv=8, d=64, max_seq_len=1 << 19, gran=(16,) * 8)  # 4096 union lists of 32768 entries
+    assert stat(huge, p, p, p, p, p, 1 << 15, 64, 256, p, None) == F.FX_ERR_SCRATCH_LIMIT
     # measurement aids
     assert lib.fx_profile_read(None, 5) == INV
     assert lib.fx_probe_read(None, 1024, p, 4, None) == INV
