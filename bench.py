@@ -377,6 +377,123 @@ def next_rows(ls: LayerSet, steps: int = 16) -> dict:
     return out
 
 
+def per_query_granularity(steps: int, warmup: int, n_layers: int = 4) -> dict:
+    """Block size and budgets chosen per decode step (Sec. 5.2 Eq. 1, Sec. 5.3 Eq. 3) on the shape of the
+    head-specific configuration (batch 4 x 128K, 32 q / 8 kv heads): the summaries of all four candidate block
+    sizes stay resident (finest level by fx_summarize, the others by fx_coarsen_summaries); every step has its
+    own seeded head properties, fx_choose_granularity turns them into gran[] / budget[] on the host, and the
+    step's layout points each KV head at its level.  Reported next to the fixed settings (16, 0.05) and
+    (32, 0.05) on the same tensors: step time, unique bytes, and the Eq. 2 output deviation from full attention."""
+    import torch
+
+    from dataclasses import replace
+
+    from paper_2605_07719_amd import fluxion as F
+    from paper_2605_07719_amd import traffic as T
+    from paper_2605_07719_amd import workloads as W
+    from paper_2605_07719_amd.harness import SummaryPyramid
+
+    shape = W.head_specific(n_layers=n_layers)
+    wl = replace(shape, name="per_query_granularity_131072x4", gran=[16] * shape.n_kv_heads,
+                 budget_frac=np.full((shape.batch, shape.n_q_heads), 0.05, dtype=np.float32))
+    B, Hq, Hkv, d = wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim
+    kw = dict(sink_tokens=wl.sink_tokens, window_tokens=wl.window_tokens)
+    l_cpu = int(max(wl.seq_len)) - wl.sink_tokens - wl.window_tokens
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    layers, build_ms = [], []
+    for layer in range(n_layers):
+        t = W.make_layer(wl, layer, device="cuda")
+        pyr = SummaryPyramid(wl)
+        if layer == 0:
+            pyr.build(t.K)  # warm-up of the two kernels
+        torch.cuda.synchronize()
+        ev0.record()
+        pyr.build(t.K)
+        ev1.record()
+        torch.cuda.synchronize()
+        build_ms.append(ev0.elapsed_time(ev1))
+        layers.append((t.q, t.K, t.V, pyr))
+    nb16 = int(W.placement(wl).n_blocks.max())
+
+    def tables(kind, layer):
+        pyr = layers[layer][3]
+        if kind == "per_step":
+            bgt0, slope, streaming = W.head_properties(Hq, seed=layer, n_kv_heads=Hkv)
+            gran, budget, _ = F.choose_granularity(Hq, Hkv, bgt0, slope, l_cpu, streaming)
+        else:
+            gran = np.full(Hkv, 16 if kind == "fixed_16_0.05" else 32, dtype=np.int32)
+            budget = np.full(Hq, 1.0 if kind == "dense" else 0.05, dtype=np.float32)
+        k_need = max(int(np.ceil(float(budget[h]) * (-(-int(max(wl.seq_len)) // int(gran[h // (Hq // Hkv)])))))
+                     for h in range(Hq))
+        return pyr.layout(gran), torch.from_numpy(np.tile(budget, (B, 1))).cuda(), gran, max(1, k_need)
+
+    sizing = layers[0][3].level_layout[16]  # the finest level needs the largest workspaces
+    out = torch.empty((B, Hq, d), dtype=torch.float32, device="cuda")
+    ws_sel = torch.empty(F.select_workspace_bytes(sizing), dtype=torch.uint8, device="cuda")
+    cnt = torch.empty((B, Hq), dtype=torch.int32, device="cuda")
+
+    def run_setting(kind, layer_ids, n_steps, n_warm):
+        tabs = [tables(kind, l) for l in layer_ids]
+        k_max = min(nb16, max(tb[3] for tb in tabs))
+        idx = torch.empty((B, Hq, k_max), dtype=torch.int32, device="cuda")
+        ws_dec = torch.empty(F.decode_workspace_bytes(sizing, k_max, wl.sink_tokens, wl.window_tokens),
+                             dtype=torch.uint8, device="cuda")
+
+        def step(i):
+            q, K, V, pyr = layers[layer_ids[i % len(layer_ids)]]
+            layout, bf, _, _ = tabs[i % len(layer_ids)]
+            F.select(layout, q, pyr.S, budget_frac=bf, k_max=k_max, idx=idx, cnt=cnt, workspace=ws_sel, **kw)
+            F.sparse_decode(layout, q, K, V, idx, cnt, k_max=k_max, out=out, workspace=ws_dec, **kw)
+
+        for i in range(n_warm):
+            step(i)
+        torch.cuda.synchronize()
+        ev0.record()
+        for i in range(n_steps):
+            step(i)
+        ev1.record()
+        torch.cuda.synchronize()
+        us = ev0.elapsed_time(ev1) / max(n_steps, 1) * 1e3
+        F.profile_enable(True)
+        acc = {k: 0.0 for k in F.PROFILE_SLOTS}
+        for i in range(len(layer_ids)):
+            step(i)
+            for k, v in F.profile_read().items():
+                acc[k] += v / len(layer_ids) * 1e3
+        F.profile_enable(False)
+        uniq = []
+        for i in range(len(layer_ids)):
+            step(i)
+            torch.cuda.synchronize()
+            gran = tabs[i][2]
+            uniq.append(T.decode_bytes(wl.seq_len, gran, Hq, d, wl.sink_tokens, wl.window_tokens, idx.cpu().numpy(),
+                                       cnt.cpu().numpy())["unique_bytes"])
+        step(0)  # leave layer_ids[0]'s output in `out`
+        torch.cuda.synchronize()
+        return {"us_per_layer_step_eager": us, "kernel_us": acc, "decode_unique_bytes": float(np.mean(uniq)),
+                "gran_per_layer": [tb[2].tolist() for tb in tabs], "k_max": k_max}, out.double().clone()
+
+    ids = list(range(n_layers))
+    _, dense = run_setting("dense", [0], 1, 0)
+    scale = dense.norm(dim=-1).amax(dim=-1, keepdim=True)
+    res = {"workload": wl.name, "layers_resident": n_layers,
+           "pyramid_build_ms_per_layer": float(np.mean(build_ms)),
+           "pyramid_levels": [16, 32, 64, 128], "settings": {}}
+    for kind in ("per_step", "fixed_16_0.05", "fixed_32_0.05"):
+        r, _ = run_setting(kind, ids, steps, warmup)
+        _, o0 = run_setting(kind, [0], 1, 0)
+        dev = (o0 - dense).norm(dim=-1) / scale
+        r["eq2_deviation_layer0"] = {"mean": float(dev.mean()), "max": float(dev.max())}
+        res["settings"][kind] = r
+    t0 = time.perf_counter()
+    for layer in range(64):
+        bgt0, slope, streaming = W.head_properties(Hq, seed=layer % n_layers, n_kv_heads=Hkv)
+        F.choose_granularity(Hq, Hkv, bgt0, slope, l_cpu, streaming)
+    res["host_tables_us_per_step"] = (time.perf_counter() - t0) / 64 * 1e6
+    return res
+
+
 def sampled_oracle(ls: LayerSet, sample, seconds: float) -> dict:
     """Outside every timed region: the GPU's layer 0 step against the oracle on the sequences `sample` (all their
     heads), and the oracle's own time for the layer-step of those sequences on this machine's host cores.
@@ -510,7 +627,7 @@ def main():
         return r, base
 
     baselines = []
-    nxt = None
+    nxt = pq = None
     if args.only:
         wl, nl, sample = extras[args.only]()
         head, base = run(LayerSet(wl, nl), sample, 3.0)
@@ -538,6 +655,13 @@ def main():
             if name == "hbm_stress":
                 nxt = next_rows(ls)
                 log("[bench] widened entry points:", json.dumps(nxt))
+            if name == "head_specific":
+                del ls
+                ls = None
+                torch.cuda.empty_cache()
+                pq = per_query_granularity(min(args.steps, 32), min(args.warmup, 8))
+                log("[bench] per-query granularity:", json.dumps(pq))
+                continue
             if name == "qwen_ragged":
                 u = union_step_times(ls, min(args.steps, 16))
                 u["attend_frac_of_hbm_peak"] = r["decode_unique_bytes"] / (u["kernel_us"]["attend"] * 1e-6) / 1e9 / HBM_PEAK_GBPS
@@ -582,6 +706,7 @@ def main():
         "roofline_32k": roofline_of(head),
         "stream_probe": probe,
         "next_rows": nxt,
+        "per_query_granularity": pq,
         "workloads": others,
         "cpu_baseline": base,
         "cpu_baseline_workloads": baselines,

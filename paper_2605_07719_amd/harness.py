@@ -74,3 +74,44 @@ class GpuProblem:
                              sink_tokens=wl.sink_tokens, window_tokens=wl.window_tokens, out=self.out,
                              workspace=self.ws_decode, group_union=group_union)
         return self.out
+
+
+class SummaryPyramid:
+    """Summaries of one layer's keys at every candidate block size, resident in one device buffer, so that a
+    decode step may use a different block size per KV head (chosen per step by fx_choose_granularity) by
+    pointing each (sequence, KV head) at the level it wants: only offsets change, no summary is rebuilt."""
+
+    def __init__(self, wl, levels=(16, 32, 64, 128), device="cuda"):
+        import torch
+
+        from . import fluxion as F
+
+        self.F, self.wl, self.device = F, wl, torch.device(device)
+        self.pyr = W.pyramid(wl, levels)
+        self.S = torch.empty((self.pyr.total_blocks, 2, wl.head_dim), dtype=torch.bfloat16, device=self.device)
+        self.level_layout = {}
+        for g in self.pyr.levels:
+            pl = self.pyr.placements[g]
+            self.level_layout[g] = F.Layout.from_host(
+                wl.n_q_heads, wl.n_kv_heads, wl.head_dim, pl.seq_len, pl.seq_base, pl.kv_head_stride,
+                pl.token_stride, pl.sum_base.reshape(-1), pl.gran, device=device)
+
+    def level_view(self, g):
+        lo = self.pyr.level_base[g]
+        return self.S[lo : lo + self.pyr.placements[g].total_blocks]
+
+    def build(self, K):
+        """fx_summarize at the finest block size, every coarser level from the finest by fx_coarsen_summaries."""
+        fine = self.pyr.levels[0]
+        self.F.summarize(self.level_layout[fine], K, self.level_view(fine))
+        for g in self.pyr.levels[1:]:
+            self.F.coarsen_summaries(self.level_layout[fine], self.level_view(fine), self.level_layout[g],
+                                     self.level_view(g))
+
+    def layout(self, gran):
+        """fx_layout of a step whose KV head j uses block size gran[j] (each a level of the pyramid)."""
+        pl = self.pyr.placements[self.pyr.levels[0]]
+        return self.F.Layout.from_host(
+            self.wl.n_q_heads, self.wl.n_kv_heads, self.wl.head_dim, pl.seq_len, pl.seq_base, pl.kv_head_stride,
+            pl.token_stride, self.pyr.sum_base(gran).reshape(-1), np.asarray(gran, dtype=np.int32),
+            device=str(self.device))

@@ -262,3 +262,49 @@ def subset(wl: Workload, tensors: LayerTensors, seqs: List[int]):
 def to_u16(t: torch.Tensor) -> np.ndarray:
     """bf16 tensor -> host uint16 bit patterns."""
     return t.detach().contiguous().cpu().view(torch.int16).numpy().view(np.uint16)
+
+
+# ---------------------------------------------------------------------------------------------------
+# Per-query granularity (Sec. 5.2, 5.3: the block size of a group is chosen per decode step from predicted
+# head properties).  The head-property predictor needs trained weights and is not part of this build; the
+# seeded draws below stand in for its outputs.  The summary pyramid keeps one set of summaries per candidate
+# block size in one buffer, so that a step's mixed block sizes are just a table of offsets.
+# ---------------------------------------------------------------------------------------------------
+
+def head_properties(n_q_heads: int, seed: int, streaming_frac: float = 0.125, n_kv_heads: int = 1):
+    """Stand-ins for the predictor's per-head outputs of one step: budget at block size 1 (`bgt0`), growth
+    per log2 of the block size (`slope`), and the streaming flag (Sec. 3.2).  Half of the heads are flat
+    (their budget hardly grows with the block size, so coarse blocks are cheap for them), half are steep;
+    a per-group factor makes some GQA groups flat as a whole, so that all candidate block sizes occur."""
+    rng = np.random.default_rng(seed + 707)
+    bgt0 = np.exp(rng.uniform(np.log(0.005), np.log(0.08), size=n_q_heads))
+    flat = rng.random(n_q_heads) < 0.5
+    slope = np.where(flat, rng.uniform(0.0, 0.003, size=n_q_heads), rng.uniform(0.008, 0.03, size=n_q_heads))
+    slope = slope * np.repeat(rng.choice([0.1, 0.35, 1.0], size=n_kv_heads), n_q_heads // n_kv_heads)
+    streaming = rng.random(n_q_heads) < streaming_frac
+    return bgt0.astype(np.float32), slope.astype(np.float32), streaming.astype(np.uint8)
+
+
+@dataclass
+class Pyramid:
+    """Summaries of one layer at several block sizes in one [total_blocks, 2, d] buffer: level g occupies the
+    blocks [level_base[g], level_base[g] + placements[g].total_blocks)."""
+
+    levels: List[int]
+    level_base: dict
+    placements: dict  # block size -> Placement with that block size for every KV head
+    total_blocks: int
+
+    def sum_base(self, gran) -> np.ndarray:
+        """int64 [batch, Hkv]: block offset of (b, j) inside the combined buffer when KV head j uses gran[j]."""
+        cols = [self.level_base[int(g)] + self.placements[int(g)].sum_base[:, j] for j, g in enumerate(gran)]
+        return np.stack(cols, axis=1).astype(np.int64)
+
+
+def pyramid(wl: Workload, levels=(16, 32, 64, 128)) -> Pyramid:
+    base, placements, off = {}, {}, 0
+    for g in levels:
+        pl = placement(replace(wl, gran=[int(g)] * wl.n_kv_heads))
+        base[int(g)], placements[int(g)] = off, pl
+        off += pl.total_blocks
+    return Pyramid(levels=[int(g) for g in levels], level_base=base, placements=placements, total_blocks=off)

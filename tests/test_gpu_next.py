@@ -182,3 +182,54 @@ def test_streaming_groups_are_skipped_and_still_correct():
     out = gp.decode().cpu().numpy().astype(np.float64)
     assert np.isfinite(out).all()
     assert np.abs(out - ref["out"]).max() < TOL
+
+
+def test_per_step_granularity_from_a_resident_pyramid():
+    """Sec. 5.2 / 5.3: the block size of a group and the budgets of its heads are chosen per decode step.  The
+    summaries of all four candidate block sizes stay resident (built once: finest level by fx_summarize, the
+    others by fx_coarsen_summaries); every step draws new head properties, fx_choose_granularity turns them
+    into gran[] / budget[], and the step's layout points each KV head at its level.  Each step is compared with
+    the oracle run at the block sizes and budgets of the oracle's own selector."""
+    from paper_2605_07719_amd.harness import SummaryPyramid
+
+    wl = base_workload(seed=27, n_q_heads=8, n_kv_heads=4, seq_len=[9000, 4111, 6500], gran=[16] * 4)
+    t = W.make_layer(wl)
+    gp = GpuProblem(wl, t)                       # q/K/V on the device, buffers sized for the finest level
+    pyr = SummaryPyramid(wl)
+    pyr.build(gp.K)
+    l_cpu = max(wl.seq_len) - wl.sink_tokens - wl.window_tokens
+    kw = dict(sink_tokens=wl.sink_tokens, window_tokens=wl.window_tokens)
+    seen = set()
+    for step in range(4):
+        bgt0, slope, streaming = W.head_properties(wl.n_q_heads, seed=step, streaming_frac=0.2, n_kv_heads=wl.n_kv_heads)
+        gran, budget, _ = F.choose_granularity(wl.n_q_heads, wl.n_kv_heads, bgt0, slope, l_cpu, streaming)
+        o_gran, o_budget, _ = OS.choose(wl.n_q_heads, wl.n_kv_heads, bgt0, slope, l_cpu, streaming)
+        assert gran.tolist() == o_gran
+        seen.update(o_gran)
+        layout = pyr.layout(gran)
+        bf = torch.from_numpy(np.tile(budget, (wl.batch, 1))).cuda()
+        F.select(layout, gp.q, pyr.S, budget_frac=bf, k_max=gp.k_max, idx=gp.idx, cnt=gp.cnt, workspace=gp.ws_select,
+                 **kw)
+        F.sparse_decode(layout, gp.q, gp.K, gp.V, gp.idx, gp.cnt, k_max=gp.k_max, out=gp.out, workspace=gp.ws_decode,
+                        **kw)
+        torch.cuda.synchronize()
+        wl_s = replace(wl, gran=o_gran, budget_frac=np.tile(np.asarray(o_budget, np.float32), (wl.batch, 1)))
+        ref = run_oracle(wl_s, t)
+        # the level each KV head reads equals the oracle's summaries at that block size
+        S_all, pl_s = W.to_u16(pyr.S), W.placement(wl_s)
+        base = pyr.pyr.sum_base(o_gran)
+        for b in range(wl.batch):
+            for j in range(wl.n_kv_heads):
+                nb = int(pl_s.n_blocks[b, j])
+                assert np.array_equal(bf16_bits_to_f64(S_all[base[b, j] : base[b, j] + nb]),
+                                      bf16_bits_to_f64(ref["S"][int(pl_s.sum_base[b, j]) : int(pl_s.sum_base[b, j]) + nb]))
+        exempt, differ = compare_selection(gp.idx.cpu().numpy(), gp.cnt.cpu().numpy(), ref["idx"][..., : gp.k_max],
+                                           ref["cnt"], ref["gap"], ref["kth"], ref["scores"], None)
+        own = O.sparse_attention(ref["L"], ref["q"], ref["K"], ref["V"], gp.idx.cpu().numpy(), gp.cnt.cpu().numpy(),
+                                 threads=THREADS, **kw)
+        err = np.abs(gp.out.cpu().numpy().astype(np.float64) - own).max()
+        print(f"  step {step}: gran {o_gran}, streaming heads {int(streaming.sum())}, near-tie heads {exempt}, "
+              f"max abs err {err:.3e}", flush=True)
+        assert err < TOL
+        assert (gp.cnt[:, streaming.astype(bool)] == 0).all()
+    assert len(seen) >= 2                          # the steps really used different block sizes
