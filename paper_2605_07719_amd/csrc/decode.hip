@@ -243,7 +243,7 @@ __device__ __forceinline__ void finish_split(Split& sp, int padded_total) {
 struct FullSlice { static constexpr bool value = true; };
 struct PartialSlice { static constexpr bool value = false; };
 
-template <int kD, int kG>
+template <int kD, int kG, bool kMfma>
 __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* __restrict__ q,
                                                      const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
                                                      const uint32_t* __restrict__ uni,
@@ -258,7 +258,7 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
   // heads on that order needs > 200 registers (2 resident waves), so a slice is processed one head at a
   // time (only one head's probabilities live) and q is re-read from LDS per head: 142-160 registers,
   // 3 resident waves (measured +4% at 7 heads per group; at 4 heads the LDS reads cost 3%).
-  constexpr bool kHeadMajor = kG >= 6;
+  constexpr bool kHeadMajor = kG >= 6 && !kMfma;
   // (Requesting the next slice before the current one is consumed costs 32 more registers and never paid
   // for the resident wave it takes away: the loads in flight come from the resident waves.)
   extern __shared__ int s_prefix[];     // [n_groups + 1] exclusive prefix of (padded) slices per group, then
@@ -268,6 +268,8 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
   __shared__ uint32_t s_ent[kEntriesPerPiece];
   __shared__ int s_claim;
   __shared__ uint4 s_q[kHeadMajor ? kG : 1][kD / 8];
+  constexpr int kStageStride = kD / 8 + 1;  // 16-byte pieces per staged K row: the row plus one piece of padding
+  __shared__ uint4 s_kstage[kMfma ? 4 : 1][kMfma ? 16 * kStageStride : 1];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int chunk = lane % kLanes, tslot = lane / kLanes;
@@ -359,6 +361,167 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
     const uint16_t* Kb = K + head_base;
     const uint16_t* Vb = V + head_base;
 
+    if constexpr (kMfma) {
+    // ---- matrix-core form of the segment (head_dim 128) ----------------------------------------------------
+    // Lane (row r = lane / 16, column c = lane % 16).  The K/V loads are the same as in the vector form: load i
+    // gives this lane channels 8c .. 8c+7 of token 4i + r of the slice.
+    //   S^T = K Q^T  (v_mfma_f32_16x16x32_bf16, 4 steps of 32 channels): the 16 K rows pass through a private,
+    //     row-padded LDS region of the wave (written as loaded, read back with lane (r, c) taking 16 bytes of
+    //     the row of token 4(c % 4) + c / 4 at piece 4 step + r), B = Q^T with head c % 8 in column c (heads
+    //     twice: columns 8..15 repeat columns 0..7).  Result register i of lane (r, c): logit of token 4i + r
+    //     for head c % 8 -- the same tokens whose V rows the lane holds.
+    //   softmax: every lane works on its own head's 4 logits; the running maximum of a head is common to all
+    //     its lanes and is only raised (one cross-row exchange, accumulators rescaled) when some logit exceeds it.
+    //   O = P V  (v_mfma_f32_16x16x16_bf16, k = 4r + i <-> token 4i + r, one instruction per channel e of the
+    //     lane's 8: column c <-> channel 8c + e): A = P, rows 0..7 the upper 16 bits of p of head c, rows 8..15
+    //     the bf16 of what that cut off (so p enters with 16 mantissa bits and the two partial outputs add up
+    //     at the end of the segment); B = V straight from the load registers (two byte permutes per channel).
+    // The arithmetic per slice does not depend on how many heads want the block.
+    static_assert(!kMfma || (kD == 128 && kG <= 8), "matrix-core path: head_dim 128, at most 8 heads per group");
+    const int r = lane >> 4, c = lane & 15;
+    const int my_head = c & 7;
+    const bool is_lo = c >= 8;
+    uint4* stage = s_kstage[wave];
+    uint4 q_op[4];
+#pragma unroll
+    for (int st = 0; st < 4; ++st) {
+      q_op[st] = make_uint4(0u, 0u, 0u, 0u);
+      if (my_head < kG)
+        q_op[st] = *reinterpret_cast<const uint4*>(q + ((int64_t)b * P.n_q_heads + j * kG + my_head) * kD + 32 * st + 8 * r);
+    }
+    f32x4_t o_acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o_acc[e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    float m_run = kNegBig, l_run = 0.f;
+    const int tau_row = (4 * (c & 3) + (c >> 2)) * kStageStride;  // LDS row of the token that MFMA row c stands for
+
+    for (int pe = e_lo; pe <= e_hi; pe += kEntriesPerPiece) {
+    __syncthreads();  // the previous piece's readers are done
+    s_ent[tid] = ent_next;
+    __syncthreads();
+    if (pe + kEntriesPerPiece + tid <= e_hi) ent_next = entries[pe + kEntriesPerPiece + tid];  // in flight during this piece
+    const int p_lo = max(l0, pe * spb), p_hi = min(l1, (pe + kEntriesPerPiece) * spb);
+
+    for (int sl = p_lo + wave; sl < p_hi; sl += 4) {
+      const int e = sl / spb;
+      const uint32_t ent = __builtin_amdgcn_readfirstlane(s_ent[e - pe]);
+      const uint32_t mask = ent & 255u;
+      const int t_first = (int)(ent >> 8) * geo.g + (sl - e * spb) * 16;  // first token of the slice
+      const int t0 = t_first + tslot;                                      // tslot == r at head_dim 128
+      uint4 kraw[kLoads], vraw[kLoads];
+#pragma unroll
+      for (int i = 0; i < kLoads; ++i) {
+        const int64_t row = (int64_t)min(t0 + i * kTPL, geo.n_tokens - 1) * P.token_stride;
+        kraw[i] = stream_load16(Kb + row);
+        vraw[i] = stream_load16(Vb + row);
+      }
+      // K rows -> LDS -> A operand.  Only this wave touches its region and a wave's LDS instructions execute in
+      // order: the fences keep the compiler from reordering across them; no barrier instruction is needed.
+#pragma unroll
+      for (int i = 0; i < kLoads; ++i) stage[(4 * i + r) * kStageStride + c] = kraw[i];
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      f32x4_t d = {0.f, 0.f, 0.f, 0.f};
+      uint4 k_op[4];
+#pragma unroll
+      for (int st = 0; st < 4; ++st) k_op[st] = stage[tau_row + 4 * st + r];
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int st = 0; st < 4; ++st)
+        d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, k_op[st]),
+                                                    __builtin_bit_cast(bf16x8_t, q_op[st]), d, 0, 0, 0);
+      // softmax of this lane's head over its 4 tokens
+      const bool active = ((mask >> my_head) & 1u) != 0u && my_head < kG;
+      bool ok[4];
+      float sp[4];
+      float mx = kNegBig;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        ok[i] = active && (t0 + i * kTPL < geo.n_tokens);
+        sp[i] = ok[i] ? d[i] : kNegBig;
+        mx = fmaxf(mx, sp[i]);
+      }
+      if (__ballot(mx > m_run)) {  // some head's maximum moves (rare once warmed up): raise it for all its lanes
+        mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * q_scale);
+        l_run *= alpha;
+        m_run = m_new;
+        // accumulator register i of this lane belongs to head-row 4r + i, i.e. head (4r + i) % 8, whose factor
+        // sits in the lanes of column (4r + i) % 8
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float a = __shfl(alpha, (4 * r + i) & 7, kWave);
+#pragma unroll
+          for (int e8 = 0; e8 < 8; ++e8) o_acc[e8][i] *= a;
+        }
+      }
+      const float m_scaled = m_run * q_scale;
+      uint32_t pbits[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float pv = ok[i] ? __builtin_amdgcn_exp2f(fmaf(sp[i], q_scale, -m_scaled)) : 0.f;
+        l_run += pv;
+        const float hi = __uint_as_float(__float_as_uint(pv) & 0xffff0000u);
+        pbits[i] = __float_as_uint(is_lo ? pv - hi : pv);  // the upper halves are packed below
+      }
+      uint2 p_op;
+      p_op.x = __builtin_amdgcn_perm(pbits[1], pbits[0], 0x07060302u);
+      p_op.y = __builtin_amdgcn_perm(pbits[3], pbits[2], 0x07060302u);
+      const s16x4_t p_vec = __builtin_bit_cast(s16x4_t, p_op);
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {  // dword w of the V registers holds channels 2w (low half) and 2w + 1
+        const uint32_t v0 = w == 0 ? vraw[0].x : w == 1 ? vraw[0].y : w == 2 ? vraw[0].z : vraw[0].w;
+        const uint32_t v1 = w == 0 ? vraw[1].x : w == 1 ? vraw[1].y : w == 2 ? vraw[1].z : vraw[1].w;
+        const uint32_t v2 = w == 0 ? vraw[2].x : w == 1 ? vraw[2].y : w == 2 ? vraw[2].z : vraw[2].w;
+        const uint32_t v3 = w == 0 ? vraw[3].x : w == 1 ? vraw[3].y : w == 2 ? vraw[3].z : vraw[3].w;
+        uint2 even, odd;
+        even.x = __builtin_amdgcn_perm(v1, v0, 0x05040100u);
+        even.y = __builtin_amdgcn_perm(v3, v2, 0x05040100u);
+        odd.x = __builtin_amdgcn_perm(v1, v0, 0x07060302u);
+        odd.y = __builtin_amdgcn_perm(v3, v2, 0x07060302u);
+        o_acc[2 * w] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_vec, __builtin_bit_cast(s16x4_t, even), o_acc[2 * w], 0, 0, 0);
+        o_acc[2 * w + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_vec, __builtin_bit_cast(s16x4_t, odd), o_acc[2 * w + 1], 0, 0, 0);
+      }
+    }
+    }  // pieces
+
+    // the claim of the next unit is requested before the last segment's reduction, which hides its latency
+    if (seg_end == s1 && tid == 0 && split.n_claimed > 0) claimed = atomicAdd(claim_counter, 1);
+
+    // ---- the wave's partial: add the two halves of p's split, sum l over the rows, hand over to the 4-wave fuse --
+    {
+      float lt = l_run;
+      lt += __shfl_xor(lt, 16, kWave);
+      lt += __shfl_xor(lt, 32, kWave);
+#pragma unroll
+      for (int e8 = 0; e8 < 8; ++e8) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          float x = o_acc[e8][i];
+          x += __shfl_xor(x, 32, kWave);  // head-row 4r + i (upper bits of p) + head-row 4r + i + 8 (the rest)
+          o_acc[e8][i] = x;
+        }
+      }
+      if (r < 2) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int head = 4 * r + i;
+          if (head < kG) {
+#pragma unroll
+            for (int e8 = 0; e8 < 8; ++e8) s_red[wave][head][c * 8 + e8] = o_acc[e8][i];
+          }
+        }
+      }
+      if (r == 0 && c < kG) {
+        s_red[wave][c][kD] = m_run;
+        s_red[wave][c][kD + 1] = lt;
+      }
+    }
+    } else {
     // q stays packed (2 bf16 per register) and unscaled (the softmax scale is applied in the exponent)
     uint4 qp[kHeadMajor ? 1 : kG];
     if constexpr (kHeadMajor) {  // visible to all waves after the barrier that precedes the first piece
@@ -517,7 +680,6 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
     if (seg_end == s1 && tid == 0 && split.n_claimed > 0) claimed = atomicAdd(claim_counter, 1);
 
     // ---- fuse the token slots of the wave, then the 4 waves, then write the segment's partial -----
-    const int slot = min(unit + grp, slots_cap - 1);  // the clamp never binds (slots_cap >= units + groups)
 #pragma unroll
     for (int r = 0; r < kG; ++r) {
       float M = m_run[r];
@@ -543,6 +705,8 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
         }
       }
     }
+    }  // vector form
+    const int slot = min(unit + grp, slots_cap - 1);  // the clamp never binds (slots_cap >= units + groups)
     __syncthreads();
     for (int x = tid; x < kG * kD; x += 256) {
       const int r = x / kD, c = x % kD;
@@ -649,6 +813,13 @@ __global__ __launch_bounds__(256) void merge_kernel(Params P, const int32_t* __r
   }
 }
 
+// Which groups take the matrix-core form of the attention kernel (head_dim 128 only).
+#ifndef FX_MFMA_MIN_GROUP
+#define FX_MFMA_MIN_GROUP 6
+#endif
+template <int kD, int kG>
+constexpr bool kUseMfma = kD == 128 && kG >= FX_MFMA_MIN_GROUP;
+
 // Resident workgroups of attend_kernel<kD, kG> per compute unit on the current device (queried once per device).
 template <int kD, int kG>
 static int attend_wg_per_cu(size_t lds) {
@@ -656,7 +827,7 @@ static int attend_wg_per_cu(size_t lds) {
   const int dev = current_device();
   int n = cached[dev].load(std::memory_order_relaxed);
   if (n == 0) {
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, attend_kernel<kD, kG>, 256, lds) != hipSuccess || n < 1) n = 1;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, attend_kernel<kD, kG, kUseMfma<kD, kG>>, 256, lds) != hipSuccess || n < 1) n = 1;
     n = n > 8 ? 8 : n;
     cached[dev].store(n, std::memory_order_relaxed);
   }
@@ -675,7 +846,7 @@ template <int kD, int kG>
 static hipError_t launch_attend(const Params& P, const void* q, const void* K, const void* V, const uint32_t* uni,
                                 const int32_t* ucount, const DecodeWorkspace& W, int32_t* sched, float* acc_part,
                                 float* ml_part, int n_cu, hipStream_t stream) {
-  hipLaunchKernelGGL((attend_kernel<kD, kG>), dim3(attend_grid<kD, kG>(P, n_cu)), dim3(256), attend_lds_bytes(P), stream,
+  hipLaunchKernelGGL((attend_kernel<kD, kG, kUseMfma<kD, kG>>), dim3(attend_grid<kD, kG>(P, n_cu)), dim3(256), attend_lds_bytes(P), stream,
                      P, (const uint16_t*)q, (const uint16_t*)K, (const uint16_t*)V, uni, ucount, W.union_cap, sched,
                      acc_part, ml_part, W.slots_cap);
   return hipGetLastError();

@@ -82,6 +82,12 @@ __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc) {
   return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), acc, false);
 }
 
+// Operand and result vectors of the matrix-core instructions used here (v_mfma_f32_16x16x32_bf16: 8 bf16 per
+// lane and operand; v_mfma_f32_16x16x16_bf16: 4 bf16 per lane and operand; both: 4 floats per lane).
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
 // Cross-lane moves inside a row of 16 lanes (DPP): every lane reads a partner, so "old" is unused.
 template <int kCtrl>
 __device__ __forceinline__ float dpp_f(float x) {

@@ -25,8 +25,6 @@
 
 namespace fx {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
-typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
 // Bound on |s~ - s| / a~.  Products of bf16 pairs are exact in fp32; a chain of 2d <= 256 fp32
 // accumulations is off by at most 256 * 2^-24 a~ = 2^-16 a~ with round-to-nearest adds and 2^-15 a~
