@@ -291,6 +291,36 @@ def test_budget_larger_than_k_max_keeps_the_best_k_max():
     assert np.abs(out - oracle_on(ref, wl, idx, cnt)).max() < TOL
 
 
+@pytest.mark.parametrize("G, gain", [(7, 0.7), (7, 1.5), (4, 0.9), (8, 1.5)])
+def test_peaky_softmax_with_large_values(G, gain):
+    """Queries aligned with one past key (its weight approaches 1, a handful of others share the rest) and
+    values four times larger than usual: the case in which rounding the probabilities to 8 mantissa bits
+    before the P V product would cost about 2^-9 * |v| = 0.03.  The matrix-core form carries p in two bf16
+    halves (16 mantissa bits); the tolerance must hold with room to spare."""
+    wl = W.Workload(name=f"peaky{G}", n_q_heads=2 * G, n_kv_heads=2, head_dim=128, seq_len=[9000, 3100], gran=[16, 32],
+                    sink_tokens=64, window_tokens=256, budget_frac=np.full((2, 2 * G), 0.3, dtype=np.float32), seed=70 + G)
+    t = W.make_layer(wl)
+    pl = W.placement(wl)
+    rng = np.random.default_rng(7)
+    for b in range(wl.batch):
+        for h in range(wl.n_q_heads):
+            row = int(pl.tok_off[b]) + int(rng.integers(0, wl.seq_len[b]))
+            t.q[b, h] = (gain * t.K[h // G, row].float() + 0.3 * t.q[b, h].float()).to(torch.bfloat16)
+    t.V = (t.V.float() * 4.0).to(torch.bfloat16)
+    ref = run_oracle(wl, t)
+    assert np.abs(ref["out"]).max() > 4.0                 # outputs really are large
+    gp = GpuProblem(wl, t, k_max=ref["k_max"])
+    gp.summarize()
+    out = gp.decode(ref["idx"], ref["cnt"]).cpu().numpy().astype(np.float64)
+    err = np.abs(out - ref["out"]).max()
+    dense_ref = O.dense_attention(ref["L"], ref["q"], ref["K"], ref["V"], threads=THREADS)
+    gp.select(budget_frac=1.0)
+    err_dense = np.abs(gp.decode().cpu().numpy().astype(np.float64) - dense_ref).max()
+    print(f"  G={G} gain={gain}: max |o| {np.abs(ref['out']).max():.2f}, max abs err {err:.3e} (sparse), {err_dense:.3e} (dense)",
+          flush=True)
+    assert err < TOL / 5 and err_dense < TOL / 5
+
+
 def test_token_major_layout():
     """K/V stored [token][kv_head][d]: same results through different strides."""
     wl = small_cases()["d128_g4"]
