@@ -402,19 +402,36 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
     if (pe + kEntriesPerPiece + tid <= e_hi) ent_next = entries[pe + kEntriesPerPiece + tid];  // in flight during this piece
     const int p_lo = max(l0, pe * spb), p_hi = min(l1, (pe + kEntriesPerPiece) * spb);
 
+    // The rows of the wave's next slice are requested before the current slice is worked on (two slices, 16 KiB,
+    // in flight per wave; 162 registers, two resident workgroups per compute unit: +2% at the dense point,
+    // where the kernel then streams as fast as a plain read of the same bytes, no change elsewhere).
+    uint4 kraw_n[kLoads], vraw_n[kLoads];
+    uint32_t ent_n = 0u;
+    auto request = [&](int sl_) {
+      const int e_ = sl_ / spb;
+      ent_n = __builtin_amdgcn_readfirstlane(s_ent[e_ - pe]);
+      const int tf_ = (int)(ent_n >> 8) * geo.g + (sl_ - e_ * spb) * 16;
+#pragma unroll
+      for (int i = 0; i < kLoads; ++i) {
+        const int64_t row = (int64_t)min(tf_ + tslot + i * kTPL, geo.n_tokens - 1) * P.token_stride;
+        kraw_n[i] = stream_load16(Kb + row);
+        vraw_n[i] = stream_load16(Vb + row);
+      }
+    };
+    if (p_lo + wave < p_hi) request(p_lo + wave);
     for (int sl = p_lo + wave; sl < p_hi; sl += 4) {
       const int e = sl / spb;
-      const uint32_t ent = __builtin_amdgcn_readfirstlane(s_ent[e - pe]);
+      const uint32_t ent = ent_n;
       const uint32_t mask = ent & 255u;
       const int t_first = (int)(ent >> 8) * geo.g + (sl - e * spb) * 16;  // first token of the slice
       const int t0 = t_first + tslot;                                      // tslot == r at head_dim 128
       uint4 kraw[kLoads], vraw[kLoads];
 #pragma unroll
       for (int i = 0; i < kLoads; ++i) {
-        const int64_t row = (int64_t)min(t0 + i * kTPL, geo.n_tokens - 1) * P.token_stride;
-        kraw[i] = stream_load16(Kb + row);
-        vraw[i] = stream_load16(Vb + row);
+        kraw[i] = kraw_n[i];
+        vraw[i] = vraw_n[i];
       }
+      if (sl + 4 < p_hi) request(sl + 4);
       // K rows -> LDS -> A operand.  Only this wave touches its region and a wave's LDS instructions execute in
       // order: the fences keep the compiler from reordering across them; no barrier instruction is needed.
 #pragma unroll
@@ -849,10 +866,9 @@ template <int kD, int kG>
 static hipError_t launch_attend(const Params& P, const void* q, const void* K, const void* V, const uint32_t* uni,
                                 const int32_t* ucount, const DecodeWorkspace& W, int32_t* sched, float* acc_part,
                                 float* ml_part, int n_cu, hipStream_t stream) {
-  hipLaunchKernelGGL((attend_kernel<kD, kG, kUseMfma<kD, kG>>), dim3(attend_grid<kD, kG>(P, n_cu)), dim3(256), attend_lds_bytes(P), stream,
-                     P, (const uint16_t*)q, (const uint16_t*)K, (const uint16_t*)V, uni, ucount, W.union_cap, sched,
-                     acc_part, ml_part, W.slots_cap);
-  return hipGetLastError();
+  return launch(attend_kernel<kD, kG, kUseMfma<kD, kG>>, dim3(attend_grid<kD, kG>(P, n_cu)), dim3(256),
+                attend_lds_bytes(P), stream, P, (const uint16_t*)q, (const uint16_t*)K, (const uint16_t*)V, uni, ucount,
+                W.union_cap, sched, acc_part, ml_part, W.slots_cap);
 }
 
 template <int kD>
@@ -892,12 +908,12 @@ hipError_t launch_decode(const Params& P, const void* q, const void* K, const vo
   float* ml_part = reinterpret_cast<float*>(ws + W.ml_off);
 
   const size_t plan_lds = (size_t)((P.nb_stride + 3) / 4) * sizeof(uint32_t);
+  hipError_t e;
   {
     ScopedSlot prof(kSlotPlan, stream);
-    hipLaunchKernelGGL(plan_kernel, dim3(P.n_kv_heads, P.batch), dim3(kPlanThreads), plan_lds, stream, P, idx, cnt, uni,
-                       ucount, W.union_cap, sched + P.batch * P.n_kv_heads + 5);
+    e = launch(plan_kernel, dim3(P.n_kv_heads, P.batch), dim3(kPlanThreads), plan_lds, stream, P, idx, cnt, uni, ucount,
+               W.union_cap, sched + P.batch * P.n_kv_heads + 5);
   }
-  hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   {
     ScopedSlot prof(kSlotAttend, stream);
@@ -908,12 +924,10 @@ hipError_t launch_decode(const Params& P, const void* q, const void* K, const vo
   if (e != hipSuccess) return e;
   ScopedSlot prof(kSlotMerge, stream);
   if (P.head_dim == 128)
-    hipLaunchKernelGGL(merge_kernel<128>, dim3(P.n_q_heads, P.batch, 128 / kMergeCols), dim3(256), 0, stream, P, (const int32_t*)sched,
-                       (const float*)acc_part, (const float*)ml_part, out, W.slots_cap);
-  else
-    hipLaunchKernelGGL(merge_kernel<64>, dim3(P.n_q_heads, P.batch, 64 / kMergeCols), dim3(256), 0, stream, P, (const int32_t*)sched,
-                       (const float*)acc_part, (const float*)ml_part, out, W.slots_cap);
-  return hipGetLastError();
+    return launch(merge_kernel<128>, dim3(P.n_q_heads, P.batch, 128 / kMergeCols), dim3(256), 0, stream, P,
+                  (const int32_t*)sched, (const float*)acc_part, (const float*)ml_part, out, W.slots_cap);
+  return launch(merge_kernel<64>, dim3(P.n_q_heads, P.batch, 64 / kMergeCols), dim3(256), 0, stream, P,
+                (const int32_t*)sched, (const float*)acc_part, (const float*)ml_part, out, W.slots_cap);
 }
 
 }  // namespace fx

@@ -5,6 +5,10 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <tuple>
+#include <type_traits>
+#include <utility>
+
 #include "fx_device.hpp"
 
 namespace fx {
@@ -19,6 +23,23 @@ inline int current_device() {
   return dev;
 }
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+// Kernel launch that returns this launch's own status (the return value of hipLaunchKernel) and leaves the
+// runtime's sticky "last error" alone: an error the caller has not yet looked at is neither cleared nor taken
+// for one of ours.  Arguments are converted to the kernel's parameter types before their addresses are taken.
+template <typename Tuple, size_t... I>
+inline void arg_pointers(Tuple& vals, void** ptrs, std::index_sequence<I...>) {
+  ((ptrs[I] = static_cast<void*>(&std::get<I>(vals))), ...);
+}
+template <typename... KArgs, typename... Args>
+inline hipError_t launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds, hipStream_t stream,
+                         Args&&... args) {
+  static_assert(sizeof...(KArgs) == sizeof...(Args), "argument count differs from the kernel's parameter count");
+  std::tuple<std::decay_t<KArgs>...> vals{static_cast<std::decay_t<KArgs>>(std::forward<Args>(args))...};
+  void* ptrs[sizeof...(KArgs) > 0 ? sizeof...(KArgs) : 1];
+  arg_pointers(vals, ptrs, std::index_sequence_for<KArgs...>{});
+  return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, lds, stream);
+}
 
 // fx_select scratch: the approximate scores (fp32, tile-major [sequence][KV head][tile][head of group][16]),
 // per (sequence, query head, tile of 16 candidates) the largest magnitude sum (fp32), and for the exact

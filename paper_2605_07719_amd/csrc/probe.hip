@@ -6,6 +6,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "fx_kernels.hpp"
+
 namespace {
 
 constexpr int kUnroll = 8;
@@ -72,27 +74,28 @@ extern "C" {
 
 fx_status fx_probe_read(const void* src, size_t bytes, void* sink, int wg_per_cu, void* stream) {
   if (!src || !sink || bytes < 16 || (reinterpret_cast<uintptr_t>(src) & 15u)) return FX_ERR_INVALID_ARG;
-  hipLaunchKernelGGL(probe_read_kernel<false>, dim3(grid_for(wg_per_cu)), dim3(256), 0,
-                     static_cast<hipStream_t>(stream), static_cast<const uint4*>(src), bytes / 16,
-                     static_cast<uint32_t*>(sink));
-  return hipGetLastError() == hipSuccess ? FX_OK : FX_ERR_HIP;
+  return fx::launch(probe_read_kernel<false>, dim3(grid_for(wg_per_cu)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                    static_cast<const uint4*>(src), bytes / 16, static_cast<uint32_t*>(sink)) == hipSuccess
+             ? FX_OK
+             : FX_ERR_HIP;
 }
 
 fx_status fx_probe_read_streaming(const void* src, size_t bytes, void* sink, int wg_per_cu, void* stream) {
   if (!src || !sink || bytes < 16 || (reinterpret_cast<uintptr_t>(src) & 15u)) return FX_ERR_INVALID_ARG;
-  hipLaunchKernelGGL(probe_read_kernel<true>, dim3(grid_for(wg_per_cu)), dim3(256), 0,
-                     static_cast<hipStream_t>(stream), static_cast<const uint4*>(src), bytes / 16,
-                     static_cast<uint32_t*>(sink));
-  return hipGetLastError() == hipSuccess ? FX_OK : FX_ERR_HIP;
+  return fx::launch(probe_read_kernel<true>, dim3(grid_for(wg_per_cu)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                    static_cast<const uint4*>(src), bytes / 16, static_cast<uint32_t*>(sink)) == hipSuccess
+             ? FX_OK
+             : FX_ERR_HIP;
 }
 
 fx_status fx_probe_copy(void* dst, const void* src, size_t bytes, int wg_per_cu, void* stream) {
   if (!src || !dst || bytes < 16 || (reinterpret_cast<uintptr_t>(src) & 15u) ||
       (reinterpret_cast<uintptr_t>(dst) & 15u))
     return FX_ERR_INVALID_ARG;
-  hipLaunchKernelGGL(probe_copy_kernel, dim3(grid_for(wg_per_cu)), dim3(256), 0, static_cast<hipStream_t>(stream),
-                     static_cast<const uint4*>(src), static_cast<uint4*>(dst), bytes / 16);
-  return hipGetLastError() == hipSuccess ? FX_OK : FX_ERR_HIP;
+  return fx::launch(probe_copy_kernel, dim3(grid_for(wg_per_cu)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                    static_cast<const uint4*>(src), static_cast<uint4*>(dst), bytes / 16) == hipSuccess
+             ? FX_OK
+             : FX_ERR_HIP;
 }
 
 }  // extern "C"

@@ -794,19 +794,18 @@ static int score_wg_per_cu(size_t lds) {
 
 // Launches the score stage: the grid kernel for small steps, else the stream kernel.
 template <int kD, bool kStaged>
-static void launch_score(const Params& P, const uint16_t* q, const uint16_t* S, float* approx, float* mag,
+static hipError_t launch_score(const Params& P, const uint16_t* q, const uint16_t* S, float* approx, float* mag,
                          const float* budget_frac, const int32_t* budget_blocks, int mag_stride, size_t lds, int n_cu,
                          hipStream_t stream) {
   const int64_t max_tiles = (int64_t)P.batch * P.n_kv_heads * mag_stride;
   const int64_t slots = (int64_t)n_cu * score_wg_per_cu<kD, kStaged>(lds);  // resident workgroups of the chip
   if (max_tiles <= 4 * slots) {  // at most one tile per wave slot
     const dim3 grid((mag_stride + 3) / 4, P.n_kv_heads, P.batch);
-    hipLaunchKernelGGL(score_grid_kernel<kD>, grid, dim3(256), 0, stream, P, q, S, approx, mag, budget_frac,
-                       budget_blocks, mag_stride);
-  } else {
-    hipLaunchKernelGGL((score_stream_kernel<kD, kStaged>), dim3((unsigned)slots), dim3(256), lds, stream, P, q, S,
-                       approx, mag, budget_frac, budget_blocks, mag_stride);
+    return launch(score_grid_kernel<kD>, grid, dim3(256), 0, stream, P, q, S, approx, mag, budget_frac, budget_blocks,
+                  mag_stride);
   }
+  return launch(score_stream_kernel<kD, kStaged>, dim3((unsigned)slots), dim3(256), lds, stream, P, q, S, approx, mag,
+                budget_frac, budget_blocks, mag_stride);
 }
 
 hipError_t launch_select(const Params& P, const void* q, const void* S, const float* budget_frac,
@@ -818,6 +817,7 @@ hipError_t launch_select(const Params& P, const void* q, const void* S, const fl
   float* mag = reinterpret_cast<float*>(ws + W.mag_off);
   uint64_t* keys = reinterpret_cast<uint64_t*>(ws + W.keys_off);
   const int mag_stride = W.mag_stride;
+  hipError_t e;
   {
     ScopedSlot prof(kSlotScore, stream);
     // Group tables of the stream kernel: 14 bytes per group, 56 KiB at the largest supported batch * n_kv_heads
@@ -831,14 +831,13 @@ hipError_t launch_select(const Params& P, const void* q, const void* S, const fl
     const uint16_t* q16 = (const uint16_t*)q;
     const uint16_t* S16 = (const uint16_t*)S;
     if (P.head_dim == 128) {
-      if (staged) launch_score<128, true>(P, q16, S16, approx, mag, budget_frac, budget_blocks, mag_stride, lds, n_cu, stream);
-      else launch_score<128, false>(P, q16, S16, approx, mag, budget_frac, budget_blocks, mag_stride, lds, n_cu, stream);
+      if (staged) e = launch_score<128, true>(P, q16, S16, approx, mag, budget_frac, budget_blocks, mag_stride, lds, n_cu, stream);
+      else e = launch_score<128, false>(P, q16, S16, approx, mag, budget_frac, budget_blocks, mag_stride, lds, n_cu, stream);
     } else {
-      if (staged) launch_score<64, true>(P, q16, S16, approx, mag, budget_frac, budget_blocks, mag_stride, lds, n_cu, stream);
-      else launch_score<64, false>(P, q16, S16, approx, mag, budget_frac, budget_blocks, mag_stride, lds, n_cu, stream);
+      if (staged) e = launch_score<64, true>(P, q16, S16, approx, mag, budget_frac, budget_blocks, mag_stride, lds, n_cu, stream);
+      else e = launch_score<64, false>(P, q16, S16, approx, mag, budget_frac, budget_blocks, mag_stride, lds, n_cu, stream);
     }
   }
-  hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   ScopedSlot prof(kSlotTopk, stream);
   const dim3 tgrid(P.n_q_heads, P.batch);
@@ -855,22 +854,22 @@ hipError_t launch_select(const Params& P, const void* q, const void* S, const fl
 #ifndef FX_TOPK_T8
 #define FX_TOPK_T8 1024  // threads up to 8192 blocks (256: +4.5 us, 512: +0.6 us)
 #endif
-#define FX_TOPK_REG(D, KPT, T) hipLaunchKernelGGL((topk_reg_kernel<D, KPT, T>), tgrid, dim3(T), 0, stream, P, A)
+#define FX_TOPK_REG(D, KPT, T) e = launch(topk_reg_kernel<D, KPT, T>, tgrid, dim3(T), 0, stream, P, A)
   if (P.head_dim == 128) {
     if (P.nb_stride <= 1024) FX_TOPK_REG(128, 4, 256);
     else if (P.nb_stride <= 2048) FX_TOPK_REG(128, 2048 / FX_TOPK_T2, FX_TOPK_T2);
     else if (P.nb_stride <= 4096) FX_TOPK_REG(128, 4096 / FX_TOPK_T4, FX_TOPK_T4);
     else if (P.nb_stride <= 8192) FX_TOPK_REG(128, 8192 / FX_TOPK_T8, FX_TOPK_T8);
-    else hipLaunchKernelGGL(topk_kernel<128>, tgrid, dim3(256), 0, stream, P, A);
+    else e = launch(topk_kernel<128>, tgrid, dim3(256), 0, stream, P, A);
   } else {
     if (P.nb_stride <= 1024) FX_TOPK_REG(64, 4, 256);
     else if (P.nb_stride <= 2048) FX_TOPK_REG(64, 2048 / FX_TOPK_T2, FX_TOPK_T2);
     else if (P.nb_stride <= 4096) FX_TOPK_REG(64, 4096 / FX_TOPK_T4, FX_TOPK_T4);
     else if (P.nb_stride <= 8192) FX_TOPK_REG(64, 8192 / FX_TOPK_T8, FX_TOPK_T8);
-    else hipLaunchKernelGGL(topk_kernel<64>, tgrid, dim3(256), 0, stream, P, A);
+    else e = launch(topk_kernel<64>, tgrid, dim3(256), 0, stream, P, A);
   }
 #undef FX_TOPK_REG
-  return hipGetLastError();
+  return e;
 }
 
 }  // namespace fx

@@ -93,10 +93,8 @@ hipError_t launch_coarsen(const Params& Pf, const Params& Pc, const void* Sf, vo
   const int blocks_per_wg = 256 / (Pc.head_dim / 8);
   dim3 grid((Pc.nb_stride + blocks_per_wg - 1) / blocks_per_wg, Pc.n_kv_heads, Pc.batch);
   if (Pc.head_dim == 128)
-    hipLaunchKernelGGL(coarsen_kernel<128>, grid, dim3(256), 0, stream, Pf, Pc, (const uint16_t*)Sf, (uint16_t*)Sc);
-  else
-    hipLaunchKernelGGL(coarsen_kernel<64>, grid, dim3(256), 0, stream, Pf, Pc, (const uint16_t*)Sf, (uint16_t*)Sc);
-  return hipGetLastError();
+    return launch(coarsen_kernel<128>, grid, dim3(256), 0, stream, Pf, Pc, (const uint16_t*)Sf, (uint16_t*)Sc);
+  return launch(coarsen_kernel<64>, grid, dim3(256), 0, stream, Pf, Pc, (const uint16_t*)Sf, (uint16_t*)Sc);
 }
 
 hipError_t launch_summarize(const Params& P, const void* K, void* S, const int32_t* prev_len, int max_new_tokens,
@@ -107,12 +105,8 @@ hipError_t launch_summarize(const Params& P, const void* K, void* S, const int32
   const int blocks = prev_len ? (max_new_tokens + 15) / 16 + 1 : P.nb_stride;
   dim3 grid((blocks + blocks_per_wg - 1) / blocks_per_wg, P.n_kv_heads, P.batch);
   if (P.head_dim == 128)
-    hipLaunchKernelGGL(summarize_kernel<128>, grid, dim3(256), 0, stream, P, (const uint16_t*)K, (uint16_t*)S,
-                       prev_len);
-  else
-    hipLaunchKernelGGL(summarize_kernel<64>, grid, dim3(256), 0, stream, P, (const uint16_t*)K, (uint16_t*)S,
-                       prev_len);
-  return hipGetLastError();
+    return launch(summarize_kernel<128>, grid, dim3(256), 0, stream, P, (const uint16_t*)K, (uint16_t*)S, prev_len);
+  return launch(summarize_kernel<64>, grid, dim3(256), 0, stream, P, (const uint16_t*)K, (uint16_t*)S, prev_len);
 }
 
 }  // namespace fx
