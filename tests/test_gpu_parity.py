@@ -173,11 +173,13 @@ def test_exact_ties_and_integer_budgets():
     assert gp.idx[0, 0, :2].tolist() == [10, 40]
 
 
-def test_short_and_degenerate_sequences():
-    """Contexts shorter than sink + window (no candidates), a one-token sequence, a partial tail block."""
-    wl = W.Workload(name="short", n_q_heads=4, n_kv_heads=2, head_dim=128, seq_len=[1, 17, 300, 321, 64],
+@pytest.mark.parametrize("n_q_heads", [4, 8, 14])
+def test_short_and_degenerate_sequences(n_q_heads):
+    """Contexts shorter than sink + window (no candidates), a one-token sequence, a partial tail block; with 2 heads
+    per group (vector form of the attention kernel) and with 4 and 7 (matrix-core form)."""
+    wl = W.Workload(name="short", n_q_heads=n_q_heads, n_kv_heads=2, head_dim=128, seq_len=[1, 17, 300, 321, 64],
                     gran=[16, 32], sink_tokens=64, window_tokens=256,
-                    budget_frac=np.full((5, 4), 0.5, dtype=np.float32), seed=11)
+                    budget_frac=np.full((5, n_q_heads), 0.5, dtype=np.float32), seed=11)
     t = W.make_layer(wl)
     ref = run_oracle(wl, t)
     gp = GpuProblem(wl, t, k_max=ref["k_max"])
