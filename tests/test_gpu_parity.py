@@ -194,6 +194,25 @@ def test_short_and_degenerate_sequences(n_q_heads):
     assert np.abs(out[:2] - dense[:2]).max() < TOL  # no candidates: dense over all valid tokens
 
 
+def test_empty_sequences_give_zero_output():
+    """Sequences of length 0 next to ordinary ones: no blocks, no candidates, nothing selected, output rows of
+    zeros (the oracle's empty token set gives zeros too); the neighbours are unaffected."""
+    wl = W.Workload(name="empty", n_q_heads=8, n_kv_heads=2, head_dim=128, seq_len=[0, 40, 0, 700, 0], gran=[16, 32],
+                    sink_tokens=16, window_tokens=64, budget_frac=np.full((5, 8), 0.5, dtype=np.float32), seed=19)
+    t = W.make_layer(wl)
+    ref = run_oracle(wl, t)
+    assert not ref["out"][[0, 2, 4]].any()
+    gp = GpuProblem(wl, t, k_max=ref["k_max"])
+    gp.summarize()
+    assert np.array_equal(bf16_bits_to_f64(W.to_u16(gp.S))[: ref["S"].shape[0]], bf16_bits_to_f64(ref["S"]))
+    idx, cnt = gp.select()
+    compare_selection(idx.cpu().numpy(), cnt.cpu().numpy(), ref["idx"], ref["cnt"], ref["gap"], ref["kth"],
+                      ref["scores"], None)
+    out = gp.decode().cpu().numpy().astype(np.float64)
+    assert not out[[0, 2, 4]].any()
+    assert np.abs(out - ref["out"]).max() < TOL
+
+
 def test_decode_accepts_arbitrary_index_lists():
     """Unsorted, duplicated, out-of-range and sink/window-overlapping entries: ignored or harmless."""
     wl = small_cases()["d128_g7_ragged"]
