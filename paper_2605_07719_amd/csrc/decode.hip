@@ -15,9 +15,12 @@
 //                  is cut into segments; the tail of the sequence is cut into small units that
 //                  workgroups claim from a counter as they finish.  Within a segment each wave takes
 //                  every fourth slice: coalesced, non-temporal 16-byte-per-lane loads of K and V rows
-//                  (each row is read once per step), fp32 dot products reduced inside
-//                  the 8/16 lanes that share a token, running (max, sum, accumulator) per head in
-//                  registers.  Per segment one partial triple per head is written, to slot
+//                  (each row is read once per step), running (max, sum, accumulator) per head in
+//                  registers.  The arithmetic comes in two forms: a vector form (fp32 dot products
+//                  reduced inside the 8/16 lanes that share a token; head_dim 64 and groups of fewer
+//                  than 4 heads) and a matrix-core form (K Q^T and P V on bf16 MFMA with fp32
+//                  accumulation; head_dim 128, 4 to 8 heads per group), described where it starts.
+//                  Per segment one partial triple per head is written, to slot
 //                  unit + group (strictly increasing along the slice sequence, hence unique).
 //   merge_kernel   per (sequence, query head): fuse the partial triples of the group's segments in
 //                  slot order (fixed order => reproducible results).
@@ -253,14 +256,14 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
   constexpr int kLanes = kD / 8;        // lanes that share one token row
   constexpr int kTPL = 64 / kLanes;     // token rows per wave-wide load
   constexpr int kLoads = 16 / kTPL;     // loads per 16-token slice
-  // Register budget.  Up to 5 heads per group every head's logits are computed first, then the softmax
+  // Register budget of the vector form.  Up to 5 heads per group every head's logits are computed first, then the softmax
   // updates, then the accumulation (most independent work in flight; 3-5 resident waves per SIMD).  From 6
   // heads on that order needs > 200 registers (2 resident waves), so a slice is processed one head at a
   // time (only one head's probabilities live) and q is re-read from LDS per head: 142-160 registers,
   // 3 resident waves (measured +4% at 7 heads per group; at 4 heads the LDS reads cost 3%).
   constexpr bool kHeadMajor = kG >= 6 && !kMfma;
-  // (Requesting the next slice before the current one is consumed costs 32 more registers and never paid
-  // for the resident wave it takes away: the loads in flight come from the resident waves.)
+  // (In the vector form, requesting the next slice before the current one is consumed costs 32 more registers
+  // and never paid for the resident wave it takes away; the matrix-core form has the registers to spare.)
   extern __shared__ int s_prefix[];     // [n_groups + 1] exclusive prefix of (padded) slices per group, then
                                         // [n_groups] per group: slices it really has | slices per block << 24
   __shared__ float s_red[4][kG][kD + 2];
