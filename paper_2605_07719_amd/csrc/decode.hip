@@ -62,6 +62,21 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Params P, const int3
       counts[r] = c < 0 ? 0 : (c > P.k_max ? P.k_max : c);
     }
   }
+  // The first piece of every head's list is requested here, by the wave that will walk it (wave r: head r), before
+  // the counts and the sequence length have arrived: its addresses need only k_max, so the entries travel together
+  // with them instead of one round trip later.  Entries past a list's count are dropped when the piece is used.
+  constexpr int kPiece = FX_PLAN_PIECE;
+  const int wave = tid >> 6, lane = tid & 63;
+  int first_piece[kPiece / 64];
+  {
+    const bool mine = wave < P.group;
+    const int32_t* list = idx + ((int64_t)b * P.n_q_heads + j * P.group + (mine ? wave : 0)) * P.k_max;
+#pragma unroll
+    for (int u = 0; u < kPiece / 64; ++u) {
+      const int e = u * 64 + lane;
+      first_piece[u] = (mine && e < P.k_max) ? list[e] : -1;
+    }
+  }
   const Geo geo = geometry(P, b, j);
   const int n_words = (geo.n_blocks + 3) >> 2;
   for (int w = tid; w < n_words; w += kPlanThreads) mask_words[w] = 0u;
@@ -75,12 +90,27 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Params P, const int3
     if (r < P.group && geo.n_cand > 0 && counts[r] == geo.n_cand) maybe_dense |= 1u << r;
   if (tid == 0) s_not_dense = 0u;
   __syncthreads();
-  // The heads' index lists are cut into pieces of FX_PLAN_PIECE entries and the pieces are dealt to the
-  // waves round-robin, so short lists of different heads are walked concurrently and a long list is shared
+  // The heads' index lists are cut into pieces of FX_PLAN_PIECE entries.  The first piece of head r belongs to
+  // wave r (above); the further pieces of long lists are dealt to the waves round-robin, so a long list is shared
   // by all waves; a lane keeps all index loads of a piece in flight before the LDS atomics that consume them.
-  const int wave = tid >> 6, lane = tid & 63;
+  // piece entries i[u] (entry number base + 64 u + lane of head r's list, -1 past the count c) -> head masks,
+  // or, for a list that may be the whole candidate range, the comparison with that range
+  auto consume = [&](int r, bool check, int base, int c, const int* i) {
+    if (check) {
+      bool ok = true;
+#pragma unroll
+      for (int u = 0; u < kPiece / 64; ++u) {
+        const int e = base + u * 64 + lane;
+        ok = ok && (e >= c || i[u] == geo.n_sink + e);
+      }
+      if (!ok) atomicOr(&s_not_dense, 1u << r);
+    } else {
+#pragma unroll
+      for (int u = 0; u < kPiece / 64; ++u)
+        if (i[u] >= 0 && i[u] < geo.n_blocks) atomicOr(&mask_words[i[u] >> 2], (1u << r) << ((i[u] & 3) * 8));
+    }
+  };
   auto walk = [&](uint32_t heads, uint32_t verify) {
-    constexpr int kPiece = FX_PLAN_PIECE;
     int piece_no = 0;
 #pragma unroll
     for (int r = 0; r < kMaxGroup; ++r) {
@@ -90,7 +120,17 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Params P, const int3
       const int64_t slot = (int64_t)b * P.n_q_heads + j * P.group + r;
       const int c = counts[r];
       const int32_t* list = idx + slot * P.k_max;
-      for (int base = 0; base < c; base += kPiece, ++piece_no) {
+      int base = 0;
+      if (r < kPlanWaves) {  // the first piece is already in wave r's registers
+        if (wave == r && c > 0) {
+          int i[kPiece / 64];
+#pragma unroll
+          for (int u = 0; u < kPiece / 64; ++u) i[u] = u * 64 + lane < c ? first_piece[u] : -1;
+          consume(r, check, 0, c, i);
+        }
+        base = kPiece;
+      }
+      for (; base < c; base += kPiece, ++piece_no) {
         if (piece_no % kPlanWaves != wave) continue;
         int i[kPiece / 64];
 #pragma unroll
@@ -98,19 +138,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Params P, const int3
           const int e = base + u * 64 + lane;
           i[u] = e < c ? list[e] : -1;
         }
-        if (check) {
-          bool ok = true;
-#pragma unroll
-          for (int u = 0; u < kPiece / 64; ++u) {
-            const int e = base + u * 64 + lane;
-            ok = ok && (e >= c || i[u] == geo.n_sink + e);
-          }
-          if (!ok) atomicOr(&s_not_dense, 1u << r);
-        } else {
-#pragma unroll
-          for (int u = 0; u < kPiece / 64; ++u)
-            if (i[u] >= 0 && i[u] < geo.n_blocks) atomicOr(&mask_words[i[u] >> 2], (1u << r) << ((i[u] & 3) * 8));
-        }
+        consume(r, check, base, c, i);
       }
     }
   };
