@@ -165,6 +165,8 @@ fx_status fx_sparse_decode(const fx_layout* layout, const void* q, const void* K
  * All calls on one GPU share that GPU's buffer: calls that may overlap in time on one GPU (different streams
  * or threads) race; serialise them or use fx_sparse_decode with a workspace each.  Nothing in the buffer needs
  * clearing between calls (the one counter that must start at zero is reset by the call's first kernel).
+ * The first call on a device looks up the buffer's device address and the kernel's occupancy (no allocation, but
+ * runtime queries): make that first call outside stream capture; later calls only enqueue kernels.
  * Other arguments and errors as fx_sparse_decode. */
 #define FX_STATIC_SCRATCH_BYTES (48u << 20)
 fx_status fx_sparse_decode_static(const fx_layout* layout, const void* q, const void* K, const void* V,
