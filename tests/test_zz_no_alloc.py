@@ -61,3 +61,53 @@ def test_static_scratch_limit_is_an_error_not_a_fault():
     assert e.value.status == F.FX_ERR_SCRATCH_LIMIT
     torch.cuda.synchronize()
     assert bool((gp.out == 7.0).all())
+
+
+def test_static_scratch_entry_point_under_graph_capture():
+    """What the entry point is for: a captured step cannot allocate.  The step (fx_select + the static-scratch
+    decode) is captured after one eager call (the first call on a device does its runtime queries) and replayed
+    with other work on the same built-in buffer in between; every replay must reproduce the eager bits."""
+    wl = W.Workload(name="static_graph", n_q_heads=8, n_kv_heads=2, head_dim=128, seq_len=[12000, 5000], gran=[32, 16],
+                    sink_tokens=64, window_tokens=256, budget_frac=np.full((2, 8), 0.1, dtype=np.float32), seed=54)
+    other = W.Workload(name="static_other", n_q_heads=4, n_kv_heads=1, head_dim=64, seq_len=[900], gran=[16],
+                       sink_tokens=16, window_tokens=64, budget_frac=np.full((1, 4), 0.5, dtype=np.float32), seed=55)
+    gps = []
+    for w in (wl, other):
+        t = W.make_layer(w)
+        gp = GpuProblem(w, t)
+        gp.summarize()
+        gp.select()
+        gps.append(gp)
+    gp, go = gps
+    bf = torch.from_numpy(wl.budget_frac.copy()).cuda()
+    kw = dict(sink_tokens=wl.sink_tokens, window_tokens=wl.window_tokens)
+
+    def step(out):
+        F.select(gp.layout, gp.q, gp.S, budget_frac=bf, k_max=gp.k_max, idx=gp.idx, cnt=gp.cnt, workspace=gp.ws_select,
+                 **kw)
+        F.sparse_decode_static(gp.layout, gp.q, gp.K, gp.V, gp.idx, gp.cnt, k_max=gp.k_max, out=out, **kw)
+
+    def disturb():
+        F.sparse_decode_static(go.layout, go.q, go.K, go.V, go.idx, go.cnt, k_max=go.k_max,
+                               sink_tokens=other.sink_tokens, window_tokens=other.window_tokens, out=go.out)
+
+    eager = torch.empty_like(gp.out)
+    step(eager)
+    torch.cuda.synchronize()
+    assert torch.equal(eager, gp.decode())            # same bits as the workspace entry point
+    out = torch.full_like(eager, float("nan"))
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            step(out)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        out.fill_(float("nan"))
+        disturb()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), rep
