@@ -42,6 +42,11 @@ def small_cases():
         "max_context_2e19": W.Workload(
             name="g", n_q_heads=2, n_kv_heads=1, head_dim=64, seq_len=[524288], gran=[16],
             sink_tokens=64, window_tokens=256, budget_frac=np.array([[0.02, 0.001]], dtype=np.float32), seed=7),
+        # the longest context through the matrix-core form of the attention kernel (head_dim 128, 4 heads per group)
+        "max_context_2e19_d128_g4": W.Workload(
+            name="l", n_q_heads=4, n_kv_heads=1, head_dim=128, seq_len=[524288], gran=[16],
+            sink_tokens=64, window_tokens=256, budget_frac=np.array([[0.02, 0.001, 0.01, 0.005]], dtype=np.float32),
+            seed=27),
         # batch * n_kv_heads at the library's limit (4096 groups): the per-group tables of the kernels' prologues
         "max_groups_4096": W.Workload(
             name="h", n_q_heads=16, n_kv_heads=8, head_dim=64,
