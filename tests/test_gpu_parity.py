@@ -391,7 +391,8 @@ def _select_intermediates(gp):
     raw = gp.ws_select.cpu().numpy()
     n_tiles = v["mag_stride"]
     a = raw[v["approx_offset"] : v["approx_offset"] + 4 * B * H * n_tiles * 16].view(np.float32)
-    a = a.reshape(B, Hkv, n_tiles, G, 16).astype(np.float64)
+    with np.errstate(invalid="ignore"):  # slots past a group's last candidate hold whatever the workspace held
+        a = a.reshape(B, Hkv, n_tiles, G, 16).astype(np.float64)
     tiles = raw[v["mag_offset"] : v["mag_offset"] + 4 * B * H * n_tiles].view(np.float32)
     tiles = tiles.reshape(B, H, n_tiles).astype(np.float64)
     approx = np.full((B, H, v["row_stride"]), np.nan)
