@@ -47,7 +47,7 @@ constexpr int kPlanThreads = 64 * kPlanWaves;
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Params P, const int32_t* __restrict__ idx,
                                                    const int32_t* __restrict__ cnt, uint32_t* __restrict__ uni,
                                                    int32_t* __restrict__ ucount, int union_cap,
-                                                   int32_t* __restrict__ claim_counter) {
+                                                   int32_t* __restrict__ claim_counter, int direct_w, int piece_cap) {
   extern __shared__ uint32_t mask_words[];  // one byte of head mask per block, 4 blocks per word
   __shared__ int scratch[kPlanWaves];
   __shared__ uint32_t s_not_dense;
@@ -185,7 +185,14 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Params P, const int3
     if (w < wave) pos += scratch[w];
     total += scratch[w];
   }
-  uint32_t* dst = uni + (int64_t)grp * union_cap;
+  // Direct mode (small steps): the list is stored cut into pieces of S = ceil(n / direct_w) entries (n = min(total,
+  // union_cap) kept entries; at most direct_w pieces, the last one shorter), piece w at the fixed place
+  // (grp * direct_w + w) * piece_cap, so that workgroup w of the attention kernel finds its work without a prefix
+  // over the groups.  S <= ceil(union_cap / direct_w) = piece_cap.
+  const int n_kept = total < union_cap ? total : union_cap;
+  const int piece_len = direct_w > 0 ? (n_kept + direct_w - 1) / direct_w : 1;
+  const float inv_piece_len = 1.0f / (float)(piece_len > 0 ? piece_len : 1);
+  uint32_t* dst = uni + (direct_w > 0 ? (int64_t)grp * direct_w * piece_cap : (int64_t)grp * union_cap);
   for (int base = w_lo; base < w_hi; base += 256) {
     uint32_t m[4];
 #pragma unroll
@@ -194,7 +201,16 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Params P, const int3
     for (int u = 0; u < 4; ++u) {
       const unsigned long long kept = __ballot(m[u] != 0u);
       const int at = pos + __popcll(kept & ((1ull << lane) - 1ull));
-      if (m[u] != 0u && at < union_cap) dst[at] = ((uint32_t)(base + u * 64 + lane) << 8) | m[u];
+      if (m[u] != 0u && at < union_cap) {
+        int where = at;
+        if (direct_w > 0) {  // at / piece_len: a float estimate, then exact integer corrections
+          int w = (int)((float)at * inv_piece_len);
+          w -= (w * piece_len > at);
+          w += ((w + 1) * piece_len <= at);
+          where = w * piece_cap + (at - w * piece_len);
+        }
+        dst[where] = ((uint32_t)(base + u * 64 + lane) << 8) | m[u];
+      }
       pos += __popcll(kept);
     }
   }
@@ -280,7 +296,8 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
                                                      const uint32_t* __restrict__ uni,
                                                      const int32_t* __restrict__ ucount, int union_cap,
                                                      int32_t* __restrict__ sched, float* __restrict__ acc_part,
-                                                     float* __restrict__ ml_part, int slots_cap) {
+                                                     float* __restrict__ ml_part, int slots_cap, int direct_w,
+                                                     int piece_cap) {
   constexpr int kLanes = kD / 8;        // lanes that share one token row
   constexpr int kTPL = 64 / kLanes;     // token rows per wave-wide load
   constexpr int kLoads = 16 / kTPL;     // loads per 16-token slice
@@ -308,7 +325,10 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
   int* s_real = s_prefix + n_groups + 1;  // a segment then starts without a round trip to list lengths and block sizes
 
   // ---- the global slice sequence and its division, computed identically by every workgroup --------
-  Split split;
+  // (not in direct mode, where the plan kernel has already cut every group's list into one piece per workgroup)
+  Split split{};
+  int total_slices = 0;
+  if (direct_w == 0) {
   {
     const int per = (n_groups + 255) / 256;
     const int g_lo = min(tid * per, n_groups), g_hi = min(g_lo + per, n_groups);
@@ -337,7 +357,7 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
     if (tid == 255) s_prefix[n_groups] = incl;  // the last thread's inclusive sum is the (padded) total
   }
   __syncthreads();
-  const int total_slices = s_prefix[n_groups];
+  total_slices = s_prefix[n_groups];
   finish_split(split, total_slices);
   if (blockIdx.x == 0) {
     for (int g = tid; g <= n_groups; g += 256) sched[g] = s_prefix[g];
@@ -348,40 +368,22 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
       sched[n_groups + 4] = split.n_static;
     }
   }
+  }
   int32_t* claim_counter = sched + n_groups + 5;  // zeroed by plan_kernel
   const float q_scale = 1.4426950408889634f * rsqrtf((float)kD);
 
   int claimed = 0;
-  int unit = blockIdx.x;
-  for (;;) {
-  int s0 = 0, s1 = 0;
-  if (unit < split.n_static + split.n_claimed) {
-    s0 = split.unit_begin(unit);
-    s1 = min(s0 + split.unit_len(unit), unit < split.n_static ? split.static_end : total_slices);
-  }
-  const bool had_work = s0 < s1;
-  int grp = 0;  // group of slice s0: the last g with s_prefix[g] <= s0 (groups without slices are skipped)
-  if (s0 < s1) {
-    int lo = 0, hi = n_groups - 1;
-    while (lo < hi) {
-      const int mid = (lo + hi + 1) >> 1;
-      if (s_prefix[mid] <= s0) lo = mid; else hi = mid - 1;
-    }
-    grp = lo;
-  }
-
-  while (s0 < s1) {
-    // ---- one segment: slices [s0, seg_end) of the sequence, all inside group `grp` ------------------
-    const int seg_end = min(s1, s_prefix[grp + 1]);
+  // ---- one segment: slices [l0, l1) of group `grp`, counted from the start of `entries` (spb slices per entry);
+  // the segment's partial goes to `slot`.  The first entries are requested up to entry `e_load_end` (exclusive),
+  // which in direct mode does not depend on the list's length, so they travel together with it.  `claim_next`:
+  // the segment ends a unit while units are being claimed (the claim is issued before the reduction).
+  auto segment = [&](int grp, const uint32_t* entries, int l0, int l1, int spb, int e_load_end, int slot,
+                     bool claim_next) {
     const int b = grp / P.n_kv_heads, j = grp % P.n_kv_heads;
-    const int spb = s_real[grp] >> 24;  // 16-token slices per block
-    // slices relative to the group's list (the end of a padded group is clipped to the list's length)
-    const int l0 = s0 - s_prefix[grp], l1 = min(seg_end - s_prefix[grp], s_real[grp] & 0xffffff);
     const int e_lo = l0 / spb, e_hi = (l1 - 1) / spb;                  // union entries touched (inclusive)
-    const uint32_t* entries = uni + (int64_t)grp * union_cap;
     // The first 256 union entries are requested here, together with q and the sequence's length and base
     // (everything a segment needs from global memory before its K/V rows: one round trip).
-    uint32_t ent_next = e_lo + tid <= e_hi ? entries[e_lo + tid] : 0u;
+    uint32_t ent_next = e_lo + tid < e_load_end ? entries[e_lo + tid] : 0u;
     struct { int g, n_tokens; } geo;
     geo.g = spb << 4;
     {
@@ -538,7 +540,7 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
     }  // pieces
 
     // the claim of the next unit is requested before the last segment's reduction, which hides its latency
-    if (seg_end == s1 && tid == 0 && split.n_claimed > 0) claimed = atomicAdd(claim_counter, 1);
+    if (claim_next && tid == 0) claimed = atomicAdd(claim_counter, 1);
 
     // ---- the wave's partial: add the two halves of p's split, sum l over the rows, hand over to the 4-wave fuse --
     {
@@ -725,7 +727,7 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
     }  // pieces
 
     // the claim of the next unit is requested before the last segment's reduction, which hides its latency
-    if (seg_end == s1 && tid == 0 && split.n_claimed > 0) claimed = atomicAdd(claim_counter, 1);
+    if (claim_next && tid == 0) claimed = atomicAdd(claim_counter, 1);
 
     // ---- fuse the token slots of the wave, then the 4 waves, then write the segment's partial -----
 #pragma unroll
@@ -754,7 +756,6 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
       }
     }
     }  // vector form
-    const int slot = min(unit + grp, slots_cap - 1);  // the clamp never binds (slots_cap >= units + groups)
     __syncthreads();
     for (int x = tid; x < kG * kD; x += 256) {
       const int r = x / kD, c = x % kD;
@@ -775,6 +776,47 @@ __global__ __launch_bounds__(256) void attend_kernel(Params P, const uint16_t* _
       }
     }
     __syncthreads();
+  };  // segment
+
+  // ---- direct mode (small steps): workgroup w of group grp takes the w-th of direct_w pieces of the group's list,
+  // which the plan kernel stored at a fixed place: no prefix over the groups, one segment, one partial.
+  if (direct_w > 0) {
+    const int grp = blockIdx.x / direct_w, w = blockIdx.x - grp * direct_w;
+    const int spb = (int)P.gran[grp % P.n_kv_heads] >> 4;
+    const int total = ucount[grp];
+    const int piece_len = (total + direct_w - 1) / direct_w;  // as the plan kernel cut the list
+    const int n_mine = max(min(total - w * piece_len, piece_len), 0);
+    segment(grp, uni + ((int64_t)grp * direct_w + w) * piece_cap, 0, n_mine * spb, spb, piece_cap, (int)blockIdx.x,
+            false);
+    return;
+  }
+
+  int unit = blockIdx.x;
+  for (;;) {
+  int s0 = 0, s1 = 0;
+  if (unit < split.n_static + split.n_claimed) {
+    s0 = split.unit_begin(unit);
+    s1 = min(s0 + split.unit_len(unit), unit < split.n_static ? split.static_end : total_slices);
+  }
+  const bool had_work = s0 < s1;
+  int grp = 0;  // group of slice s0: the last g with s_prefix[g] <= s0 (groups without slices are skipped)
+  if (s0 < s1) {
+    int lo = 0, hi = n_groups - 1;
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (s_prefix[mid] <= s0) lo = mid; else hi = mid - 1;
+    }
+    grp = lo;
+  }
+
+  while (s0 < s1) {
+    const int seg_end = min(s1, s_prefix[grp + 1]);
+    const int spb = s_real[grp] >> 24;  // 16-token slices per block
+    // slices relative to the group's list (the end of a padded group is clipped to the list's length)
+    const int l0 = s0 - s_prefix[grp], l1 = min(seg_end - s_prefix[grp], s_real[grp] & 0xffffff);
+    segment(grp, uni + (int64_t)grp * union_cap, l0, l1, spb, (l1 - 1) / spb + 1,
+            min(unit + grp, slots_cap - 1),  // the clamp never binds (slots_cap >= units + groups)
+            seg_end == s1 && split.n_claimed > 0);
     s0 = seg_end;
     do ++grp; while (grp < n_groups && s_prefix[grp + 1] <= s0);  // next group that has slices
   }
@@ -804,7 +846,7 @@ template <int kD>
 __global__ __launch_bounds__(256) void merge_kernel(Params P, const int32_t* __restrict__ sched,
                                                     const float* __restrict__ acc_part,
                                                     const float* __restrict__ ml_part, float* __restrict__ out,
-                                                    int slots_cap) {
+                                                    int slots_cap, int direct_w) {
   constexpr int kLanesC = kMergeCols / 4;  // threads per partial (4 channels each)
   constexpr int kRows = 256 / kLanesC;     // partials in flight per iteration
   __shared__ float s_o[kRows][kMergeCols + 1];
@@ -812,9 +854,11 @@ __global__ __launch_bounds__(256) void merge_kernel(Params P, const int32_t* __r
   const int b = blockIdx.y, h = blockIdx.x, c0 = blockIdx.z * kMergeCols, tid = threadIdx.x;
   const int G = P.group, j = h / G, r = h % G;
   const int grp = b * P.n_kv_heads + j;
-  const int first = sched[grp], last = sched[grp + 1];
   int p0 = 0, p1 = 0;
-  if (last > first) {
+  if (direct_w > 0) {  // one partial per workgroup of the attention kernel, direct_w of them per group
+    p0 = grp * direct_w;
+    p1 = p0 + direct_w;
+  } else if (const int first = sched[grp], last = sched[grp + 1]; last > first) {
     const int32_t* sp_raw = sched + P.batch * P.n_kv_heads + 1;
     Split split;
     split.unit_s = sp_raw[0];
@@ -893,23 +937,49 @@ static int attend_grid(const Params& P, int n_cu) {
   return grid > kMaxUnits ? kMaxUnits : grid;
 }
 
+// Direct mode of the decode stage, for small steps: the host can bound every group's slice count from k_max alone
+// (union_cap entries of at most max_spb slices); if that bound leaves at most kDirectMaxSlices slices to each of
+// the `w` workgroups a group can have, the plan kernel stores every group's list cut into w pieces at fixed
+// places and the attention kernel needs neither the prefix over the groups nor the slice-sequence split: one
+// dependent round trip less before the first K/V rows, and the merge kernel finds its partials without the
+// split description.  w = 0: not used.
+constexpr int kDirectMaxSlices = 32;
+struct DirectMode {
+  int w = 0, piece_cap = 0;
+};
+static DirectMode direct_mode(const Params& P, const DecodeWorkspace& W, int n_wg) {
+  const int n_groups = P.batch * P.n_kv_heads;
+  if (n_groups > n_wg) return {};
+  int max_spb = 1;
+  for (int j = 0; j < P.n_kv_heads; ++j) max_spb = max_spb > (P.gran[j] >> 4) ? max_spb : (P.gran[j] >> 4);
+  const int64_t bound = (int64_t)W.union_cap * max_spb;  // slices a group can have at most
+  int w = n_wg / n_groups;
+  const int64_t enough = (bound + 3) / 4;                // pieces of at least 4 slices at the bound
+  if (w > enough) w = (int)enough;
+  if (w < 1) w = 1;
+  const int piece_cap = (W.union_cap + w - 1) / w;
+  if ((int64_t)piece_cap * max_spb > kDirectMaxSlices || piece_cap > kEntriesPerPiece) return {};
+  return {w, piece_cap};
+}
+
 template <int kD, int kG>
 static hipError_t launch_attend(const Params& P, const void* q, const void* K, const void* V, const uint32_t* uni,
                                 const int32_t* ucount, const DecodeWorkspace& W, int32_t* sched, float* acc_part,
-                                float* ml_part, int n_cu, hipStream_t stream) {
-  return launch(attend_kernel<kD, kG, kUseMfma<kD, kG>>, dim3(attend_grid<kD, kG>(P, n_cu)), dim3(256),
-                attend_lds_bytes(P), stream, P, (const uint16_t*)q, (const uint16_t*)K, (const uint16_t*)V, uni, ucount,
-                W.union_cap, sched, acc_part, ml_part, W.slots_cap);
+                                float* ml_part, int n_cu, DirectMode dm, hipStream_t stream) {
+  const int grid = dm.w > 0 ? P.batch * P.n_kv_heads * dm.w : attend_grid<kD, kG>(P, n_cu);
+  return launch(attend_kernel<kD, kG, kUseMfma<kD, kG>>, dim3(grid), dim3(256), attend_lds_bytes(P), stream, P,
+                (const uint16_t*)q, (const uint16_t*)K, (const uint16_t*)V, uni, ucount, W.union_cap, sched, acc_part,
+                ml_part, W.slots_cap, dm.w, dm.piece_cap);
 }
 
 template <int kD>
 static hipError_t dispatch_group(const Params& P, const void* q, const void* K, const void* V, const uint32_t* uni,
                                  const int32_t* ucount, const DecodeWorkspace& W, int32_t* sched, float* acc_part,
-                                 float* ml_part, int n_cu, hipStream_t stream) {
+                                 float* ml_part, int n_cu, DirectMode dm, hipStream_t stream) {
   switch (P.group) {
 #define FX_CASE(G) \
   case G:          \
-    return launch_attend<kD, G>(P, q, K, V, uni, ucount, W, sched, acc_part, ml_part, n_cu, stream);
+    return launch_attend<kD, G>(P, q, K, V, uni, ucount, W, sched, acc_part, ml_part, n_cu, dm, stream);
     FX_CASE(1) FX_CASE(2) FX_CASE(3) FX_CASE(4) FX_CASE(5) FX_CASE(6) FX_CASE(7) FX_CASE(8)
 #undef FX_CASE
   }
@@ -939,26 +1009,27 @@ hipError_t launch_decode(const Params& P, const void* q, const void* K, const vo
   float* ml_part = reinterpret_cast<float*>(ws + W.ml_off);
 
   const size_t plan_lds = (size_t)((P.nb_stride + 3) / 4) * sizeof(uint32_t);
+  const DirectMode dm = direct_mode(P, W, attend_launch_size(P, n_cu));
   hipError_t e;
   {
     ScopedSlot prof(kSlotPlan, stream);
     e = launch(plan_kernel, dim3(P.n_kv_heads, P.batch), dim3(kPlanThreads), plan_lds, stream, P, idx, cnt, uni, ucount,
-               W.union_cap, sched + P.batch * P.n_kv_heads + 5);
+               W.union_cap, sched + P.batch * P.n_kv_heads + 5, dm.w, dm.piece_cap);
   }
   if (e != hipSuccess) return e;
   {
     ScopedSlot prof(kSlotAttend, stream);
     e = P.head_dim == 128
-            ? dispatch_group<128>(P, q, K, V, uni, ucount, W, sched, acc_part, ml_part, n_cu, stream)
-            : dispatch_group<64>(P, q, K, V, uni, ucount, W, sched, acc_part, ml_part, n_cu, stream);
+            ? dispatch_group<128>(P, q, K, V, uni, ucount, W, sched, acc_part, ml_part, n_cu, dm, stream)
+            : dispatch_group<64>(P, q, K, V, uni, ucount, W, sched, acc_part, ml_part, n_cu, dm, stream);
   }
   if (e != hipSuccess) return e;
   ScopedSlot prof(kSlotMerge, stream);
   if (P.head_dim == 128)
     return launch(merge_kernel<128>, dim3(P.n_q_heads, P.batch, 128 / kMergeCols), dim3(256), 0, stream, P,
-                  (const int32_t*)sched, (const float*)acc_part, (const float*)ml_part, out, W.slots_cap);
+                  (const int32_t*)sched, (const float*)acc_part, (const float*)ml_part, out, W.slots_cap, dm.w);
   return launch(merge_kernel<64>, dim3(P.n_q_heads, P.batch, 64 / kMergeCols), dim3(256), 0, stream, P,
-                (const int32_t*)sched, (const float*)acc_part, (const float*)ml_part, out, W.slots_cap);
+                (const int32_t*)sched, (const float*)acc_part, (const float*)ml_part, out, W.slots_cap, dm.w);
 }
 
 }  // namespace fx

@@ -77,6 +77,7 @@ struct DecodeWorkspace {
   int32_t union_cap;  // entries per group in the union list
   int32_t slots_cap;  // partial-result slots: units + groups
   size_t union_off;   // uint32 [n_groups][union_cap]   (block << 8) | head mask, ascending by block
+                      // (direct mode: [n_groups][w][piece_cap], the same entries cut into w pieces per group)
   size_t ucount_off;  // int32  [n_groups]              entries per group
   size_t sched_off;   // int32  [n_groups + 8]          exclusive slice prefix, total, the split (4 values), claim counter
   size_t acc_off;     // float  [slots_cap][group][d]   un-normalised partial outputs
@@ -101,7 +102,8 @@ inline DecodeWorkspace carve_decode(const Params& P, int max_units = kMaxUnits) 
   W.union_cap = (int32_t)ucap;
   W.slots_cap = (int32_t)slots;
   size_t off = 0;
-  W.union_off = off;  off += align_up((size_t)n_groups * ucap * sizeof(uint32_t));
+  // (+ room for rounding: in direct mode the lists are stored in w pieces of ceil(ucap / w) entries per group)
+  W.union_off = off;  off += align_up(((size_t)n_groups * ucap + 2 * (size_t)kMaxUnits) * sizeof(uint32_t));
   W.ucount_off = off; off += align_up((size_t)n_groups * sizeof(int32_t));
   W.sched_off = off;  off += align_up((size_t)(n_groups + 8) * sizeof(int32_t));
   W.acc_off = off;    off += align_up((size_t)slots * P.group * P.head_dim * sizeof(float));
